@@ -1,0 +1,189 @@
+"""ctypes front-end of the CPU oracle (``symph_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the benchmark's CPU-baseline leg may import
+this; the product package never does, and this module never imports the product package.
+
+Arrays are numpy: bf16 tensors travel as ``uint16`` bit patterns, fp32 tensors as ``float32``.  A K or V pool
+is a C-contiguous array ``[L][n_blocks][bs][H_kv][d]`` (or ``[n_blocks][bs][H_kv][d]`` for a single layer).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "symph_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, -O2, OpenMP on the outermost loops)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", tmp, _SRC,
+                               "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = C.CDLL(_LIB)
+        i32, i64, vp, f32 = C.c_int32, C.c_int64, C.c_void_p, C.c_float
+        lib.oracle_num_threads.restype = C.c_int
+        lib.oracle_kv_buffer_bytes.restype = i64
+        lib.oracle_kv_buffer_bytes.argtypes = [i32, i32, i32, i32, i64]
+        lib.oracle_kv_locate.restype = None
+        lib.oracle_kv_locate.argtypes = [i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, vp, vp]
+        for fn in (lib.oracle_kv_pack, lib.oracle_kv_unpack):
+            fn.restype = C.c_int
+            fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp]
+        lib.oracle_prefix_prefill_attn.restype = C.c_int
+        lib.oracle_prefix_prefill_attn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                                   i32, i32, i32, f32, vp, i32, vp]
+        lib.oracle_attn_row_weights.restype = C.c_int
+        lib.oracle_attn_row_weights.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                                i32, i32, f32, i32, i32, i32, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _check(a: np.ndarray, dtype=None, name="array") -> np.ndarray:
+    if not isinstance(a, np.ndarray) or not a.flags.c_contiguous:
+        raise ValueError(f"{name} must be a C-contiguous numpy array")
+    if dtype is not None and a.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {a.dtype}")
+    return a
+
+
+def _pool_geometry(k_pool: np.ndarray, v_pool: np.ndarray) -> Tuple[int, int, int, int, int, int, int, int]:
+    """(L, n_blocks, bs, H_kv, d, elem_bytes, layer_stride, block_stride) of dense pools."""
+    _check(k_pool, name="k_pool")
+    _check(v_pool, name="v_pool")
+    if k_pool.shape != v_pool.shape or k_pool.dtype != v_pool.dtype:
+        raise ValueError("K and V pools must agree in shape and dtype")
+    if k_pool.dtype not in (np.uint16, np.float32):
+        raise ValueError("pools are uint16 (bf16 bits) or float32")
+    shape = k_pool.shape if k_pool.ndim == 5 else (1,) + tuple(k_pool.shape)
+    if len(shape) != 5:
+        raise ValueError("pool must be [L][n_blocks][bs][H_kv][d] or [n_blocks][bs][H_kv][d]")
+    L, nb, bs, hkv, d = (int(x) for x in shape)
+    block_stride = bs * hkv * d
+    return L, nb, bs, hkv, d, k_pool.dtype.itemsize, nb * block_stride, block_stride
+
+
+def kv_buffer_bytes(n_layers: int, n_kv_heads: int, head_dim: int, elem_bytes: int, total_tokens: int) -> int:
+    return int(_load().oracle_kv_buffer_bytes(n_layers, n_kv_heads, head_dim, elem_bytes, total_tokens))
+
+
+def kv_locate(layer_stride: int, block_stride: int, n_layers: int, block_size: int, n_kv_heads: int, head_dim: int,
+              table: np.ndarray, prefix_lens: np.ndarray, offsets: np.ndarray, s: int, l: int, kv: int, t: int
+              ) -> Tuple[int, int]:
+    """(pool element offset, buffer element offset) of one token row."""
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    pe, be = C.c_int64(), C.c_int64()
+    _load().oracle_kv_locate(layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim, _ptr(table),
+                             table.shape[1], _ptr(prefix_lens), _ptr(offsets), s, l, kv, t, C.byref(pe), C.byref(be))
+    return int(pe.value), int(be.value)
+
+
+def kv_pack(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+            offsets: np.ndarray) -> np.ndarray:
+    """Gather every session's cached K,V into a new migration buffer (1-D array of the pool dtype)."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    S = prefix_lens.shape[0]
+    n_elems = int(offsets[S]) * 2 * L * hkv * d
+    buf = np.zeros(n_elems, dtype=k_pool.dtype)
+    rc = _load().oracle_kv_pack(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, _ptr(table), table.shape[1],
+                                _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_pack failed")
+    return buf
+
+
+def kv_unpack(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+              offsets: np.ndarray, buf: np.ndarray) -> None:
+    """Scatter a migration buffer into the pools (modified in place) through ``table``."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    buf = _check(buf, k_pool.dtype, "buf")
+    S = prefix_lens.shape[0]
+    if buf.size != int(offsets[S]) * 2 * L * hkv * d:
+        raise ValueError("buffer size does not match the sessions")
+    rc = _load().oracle_kv_unpack(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, _ptr(table),
+                                  table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_unpack failed")
+
+
+def _attn_args(k_pool, v_pool, q, k_new, v_new, cu_new_lens, prefix_lens, table):
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    for a, n in ((q, "q"), (k_new, "k_new"), (v_new, "v_new")):
+        _check(a, k_pool.dtype, n)
+    cu_new_lens = _check(cu_new_lens, np.int32, "cu_new_lens")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    table = _check(table, np.int32, "table")
+    T, hq, dq = q.shape
+    if dq != d or k_new.shape != (T, hkv, d) or v_new.shape != (T, hkv, d):
+        raise ValueError("q / k_new / v_new shapes do not match the pool")
+    if int(cu_new_lens[-1]) != T:
+        raise ValueError("cu_new_lens[-1] must equal the number of query rows")
+    return L, bs, hkv, d, eb, ls, bst, T, hq
+
+
+def prefix_prefill_attn(k_pool: np.ndarray, v_pool: np.ndarray, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray,
+                        cu_new_lens: np.ndarray, prefix_lens: np.ndarray, table: np.ndarray, scale: float,
+                        layer: int = 0, token_subset: Optional[Sequence[int]] = None) -> np.ndarray:
+    """fp64 softmax attention of the new turn over [cached prefix ; causal new tokens]: ``[T][H_q][d]`` float64.
+
+    With ``token_subset`` only those global token rows are computed (all heads); other rows are NaN.
+    """
+    L, bs, hkv, d, eb, ls, bst, T, hq = _attn_args(k_pool, v_pool, q, k_new, v_new, cu_new_lens, prefix_lens, table)
+    out = np.full((T, hq, d), np.nan, dtype=np.float64)
+    sub = None
+    n_sub = 0
+    if token_subset is not None:
+        sub = np.ascontiguousarray(np.asarray(token_subset, dtype=np.int32))
+        n_sub = int(sub.size)
+    rc = _load().oracle_prefix_prefill_attn(
+        _ptr(k_pool), _ptr(v_pool), ls, bst, layer, bs, hkv, d, 1 if eb == 2 else 0, _ptr(q), _ptr(k_new),
+        _ptr(v_new), _ptr(cu_new_lens), _ptr(prefix_lens), _ptr(table), table.shape[1], prefix_lens.shape[0], hq,
+        np.float32(scale), _ptr(sub), n_sub, _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle_prefix_prefill_attn: bad argument")
+    return out
+
+
+def attn_row_weights(k_pool, v_pool, q, k_new, v_new, cu_new_lens, prefix_lens, table, scale: float, s: int, i: int,
+                     h: int, layer: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Softmax weights (length P_s + i + 1) and output row (length d) of one query row."""
+    L, bs, hkv, d, eb, ls, bst, T, hq = _attn_args(k_pool, v_pool, q, k_new, v_new, cu_new_lens, prefix_lens, table)
+    w = np.zeros(int(prefix_lens[s]) + i + 1, dtype=np.float64)
+    o = np.zeros(d, dtype=np.float64)
+    _load().oracle_attn_row_weights(
+        _ptr(k_pool), _ptr(v_pool), ls, bst, layer, bs, hkv, d, 1 if eb == 2 else 0, _ptr(q), _ptr(k_new),
+        _ptr(v_new), _ptr(cu_new_lens), _ptr(prefix_lens), _ptr(table), table.shape[1], hq, np.float32(scale), s, i,
+        h, _ptr(w), _ptr(o))
+    return w, o

@@ -1,0 +1,48 @@
+"""The pins must bite: plant one plausible mistake at a time in a COPY of the oracle (on the CPU) and check
+that the pin suite fails for it.  The real oracle is never touched."""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+MUTATIONS = {
+    # name: (text in symph_oracle.c, replacement)
+    "kv_order_swapped_in_buffer": ("((int64_t)2 * l + kv) * prefix_lens[s]", "((int64_t)2 * l + 1 - kv) * prefix_lens[s]"),
+    "buffer_token_major_instead_of_layer_major": ("(offsets[s] * 2 * n_layers + ((int64_t)2 * l + kv) * prefix_lens[s] + t) * row",
+                                                  "((offsets[s] + t) * 2 * n_layers + ((int64_t)2 * l + kv)) * row"),
+    "slot_index_wrong": ("const int64_t o = t % block_size;\n  *pool_elem", "const int64_t o = (t + 1) % block_size;\n  *pool_elem"),
+    "gqa_head_modulo": ("const int32_t g = h / G;", "const int32_t g = h % n_kv_heads;"),
+    "causal_excludes_self": ("const int64_t n_keys = (int64_t)P + i + 1;", "const int64_t n_keys = (int64_t)P + i;"),
+    "causal_sees_future": ("const int64_t n_keys = (int64_t)P + i + 1;", "const int64_t n_keys = (int64_t)P + i + 2;"),
+    "scale_dropped": ("x[j] = scale * dot;", "x[j] = dot;"),
+    "no_normalisation": ("const double p = x[j] / Z;", "const double p = x[j];"),
+    "v_read_from_k": ("const void* vb = in_pool ? v_base : v_new;", "const void* vb = in_pool ? k_base : k_new;"),
+    "new_keys_offset_wrong": ("*elem = (((int64_t)cu_s + (j - P)) * n_kv_heads + g) * head_dim;",
+                              "*elem = (((int64_t)(j - P)) * n_kv_heads + g) * head_dim;"),
+    "bf16_widen_shift": ("<< 16;\n    float f;", "<< 15;\n    float f;"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_pins_fail_on_planted_mistake(tmp_path, name):
+    old, new = MUTATIONS[name]
+    src = open(os.path.join(ROOT, "oracle", "symph_oracle.c")).read()
+    assert src.count(old) == 1, f"mutation anchor for {name} not found exactly once"
+    mroot = tmp_path / "root"
+    (mroot / "oracle").mkdir(parents=True)
+    shutil.copy(os.path.join(ROOT, "oracle", "__init__.py"), mroot / "oracle" / "__init__.py")
+    (mroot / "oracle" / "symph_oracle.c").write_text(src.replace(old, new))
+    shutil.copytree(os.path.join(ROOT, "workloads"), mroot / "workloads")
+    (mroot / "tests").mkdir()
+    shutil.copytree(os.path.join(ROOT, "tests", "golden"), mroot / "tests" / "golden")
+    for f in ("conftest.py", "test_oracle_pins.py"):
+        shutil.copy(os.path.join(ROOT, "tests", f), mroot / "tests" / f)
+    env = dict(os.environ, PYTHONPATH=str(mroot), OMP_NUM_THREADS="2")
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "tests/test_oracle_pins.py"],
+                       cwd=str(mroot), env=env, capture_output=True, text=True, timeout=300)
+    # 1 = a pin failed; a negative code = the mutant ran off its own scratch array and was aborted: caught too
+    assert r.returncode != 0, f"pins did not catch {name}:\n{r.stdout[-2000:]}\n{r.stderr[-2000:]}"

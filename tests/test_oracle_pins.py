@@ -1,0 +1,412 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something other than itself.
+
+pack / unpack (a permutation copy; Symphony Sec. 3.2 node manager, Sec. 3.3 memory management, Sec. 3.5):
+  * tagged pools: every pool element carries its own coordinates, so each buffer element can be decoded and
+    checked against the layout rules without recomputing any offset;
+  * a numpy route (take blocks, reshape, concatenate) for the whole buffer;
+  * the identity-table special case, which is a plain memcpy;
+  * round trips and sentinel bytes;
+  * the cache sizes the paper prints (tests/golden/kv_cache_sizes.txt).
+attention (Sec. 2.1: A_h = softmax(Q K^T / sqrt(d)), y = concat_h A_h V_h; causal because a token needs the keys
+and values of all prior tokens only):
+  * brute force: contiguous K,V rebuilt token by token, full (P+N)^2 causal score matrix, scipy softmax;
+  * torch's scaled_dot_product_attention in fp64 (library routine), MHA (G = 1) and GQA;
+  * cached-prefix result == full recompute; split-point invariance; block-id permutation invariance;
+  * weights sum to one; closed forms (equal keys, constant V, one dominant key, single token).
+"""
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------------------------------------
+# helpers that do NOT use the oracle
+# --------------------------------------------------------------------------------------------------------
+def to_f64(a: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns / fp32 through torch's own conversion (a library route)."""
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    return a.astype(np.float64)
+
+
+def contiguous_kv(pool: np.ndarray, table_row: np.ndarray, P: int, new: np.ndarray) -> np.ndarray:
+    """[P+N][H_kv][d] fp64 for one session, rebuilt token by token (slow on purpose)."""
+    bs = pool.shape[1]
+    rows = [pool[table_row[t // bs], t % bs] for t in range(P)]
+    rows += [new[i] for i in range(new.shape[0])]
+    return to_f64(np.stack(rows)) if rows else np.zeros((0,) + pool.shape[2:])
+
+
+def brute_force_attention(k_pool, v_pool, q, k_new, v_new, sess: W.SessionBatch, scale: float) -> np.ndarray:
+    cfg = sess.cfg
+    G = cfg.group
+    out = np.zeros(q.shape, dtype=np.float64)
+    sc = float(np.float32(scale))
+    for s in range(sess.n_sessions):
+        P, N = int(sess.prefix_lens[s]), int(sess.new_lens[s])
+        a, b = int(sess.cu_new_lens[s]), int(sess.cu_new_lens[s + 1])
+        if N == 0:
+            continue
+        K = contiguous_kv(k_pool, sess.block_table[s], P, k_new[a:b])
+        V = contiguous_kv(v_pool, sess.block_table[s], P, v_new[a:b])
+        # queries for every position: only the last N exist; earlier rows are dummies that are discarded
+        Qn = to_f64(q[a:b])
+        n = P + N
+        causal = np.tril(np.ones((n, n), dtype=bool))
+        for h in range(cfg.n_q_heads):
+            g = h // G
+            Qfull = np.zeros((n, cfg.head_dim))
+            Qfull[P:] = Qn[:, h]
+            scores = sc * (Qfull @ K[:, g].T)
+            scores = np.where(causal, scores, -np.inf)
+            A = scipy.special.softmax(scores, axis=1)
+            out[a:b, h] = (A @ V[:, g])[P:]
+    return out
+
+
+def small_cfg(dtype="bf16", **kw):
+    base = dict(name="pin", index=9, dtype=dtype, n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=8, block_size=4,
+                n_blocks=40, n_sessions=3, prefix_dist=("uniform", 1, 19), new_dist=("uniform", 1, 7), sigma=1.0,
+                scale=1.0 / np.sqrt(8.0))
+    base.update(kw)
+    return W.WorkloadConfig(**base)
+
+
+# --------------------------------------------------------------------------------------------------------
+# pack / unpack
+# --------------------------------------------------------------------------------------------------------
+def tagged_pools(cfg):
+    """fp32-sized pools whose 32-bit patterns encode (kv, layer, block, slot, head, dim)."""
+    L, nb, bs, H, d = cfg.n_layers, cfg.n_blocks, cfg.block_size, cfg.n_kv_heads, cfg.head_dim
+    l, b, o, g, c = np.meshgrid(np.arange(L), np.arange(nb), np.arange(bs), np.arange(H), np.arange(d), indexing="ij")
+
+    def tag(kv):
+        t = (((((kv * L + l) * nb + b) * bs + o) * H + g) * d + c).astype(np.uint32)
+        return t.view(np.float32).copy()
+    return tag(0), tag(1)
+
+
+def decode_tag(t, cfg):
+    L, nb, bs, H, d = cfg.n_layers, cfg.n_blocks, cfg.block_size, cfg.n_kv_heads, cfg.head_dim
+    t = t.astype(np.int64)
+    c = t % d; t //= d
+    g = t % H; t //= H
+    o = t % bs; t //= bs
+    b = t % nb; t //= nb
+    l = t % L; t //= L
+    return t, l, b, o, g, c   # t is now kv
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_pack_tagged_pool_layout(oracle_mod, seed):
+    cfg = small_cfg("fp32", n_sessions=4, prefix_dist=("uniform", 0, 23))
+    sess = W.make_sessions(cfg, seed)
+    k_pool, v_pool = tagged_pools(cfg)
+    buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert buf.size * 4 == sess.payload_bytes()
+    kv, l, b, o, g, c = decode_tag(buf.view(np.uint32), cfg)
+    # walk the buffer in order and state what each position must hold, from the layout rules alone
+    pos = 0
+    H, d, bs = cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+    for s in range(sess.n_sessions):
+        P = int(sess.prefix_lens[s])
+        for layer in range(cfg.n_layers):
+            for which in (0, 1):
+                for t in range(P):
+                    sl = slice(pos, pos + H * d)
+                    assert np.all(kv[sl] == which) and np.all(l[sl] == layer)
+                    assert np.all(b[sl] == sess.block_table[s, t // bs]) and np.all(o[sl] == t % bs)
+                    assert np.array_equal(g[sl], np.repeat(np.arange(H), d))
+                    assert np.array_equal(c[sl], np.tile(np.arange(d), H))
+                    pos += H * d
+    assert pos == buf.size
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_pack_matches_numpy_take_route(oracle_mod, dtype):
+    cfg = small_cfg(dtype, n_sessions=5, n_layers=3, n_blocks=64, prefix_dist=("uniform", 0, 30))
+    sess = W.make_sessions(cfg, 11)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 5)
+    pieces = []
+    nblk = sess.blocks_per_session()
+    for s in range(sess.n_sessions):
+        P = int(sess.prefix_lens[s])
+        ids = sess.block_table[s, : nblk[s]]
+        for layer in range(cfg.n_layers):
+            for pool in (k_pool, v_pool):
+                pieces.append(np.take(pool[layer], ids, axis=0).reshape(-1, cfg.row_elems)[:P].ravel())
+    expect = np.concatenate(pieces) if pieces else np.zeros(0, k_pool.dtype)
+    got = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert got.tobytes() == expect.tobytes()
+
+
+def test_pack_identity_table_is_memcpy(oracle_mod):
+    cfg = small_cfg("bf16", n_layers=1, n_sessions=1, n_blocks=8, prefix_dist=("const", 32), fresh_tables=False)
+    sess = W.make_sessions(cfg, 3)
+    sess.block_table[0, :] = np.arange(8, dtype=np.int32)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 3)
+    got = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert got.tobytes() == k_pool.tobytes() + v_pool.tobytes()
+
+
+def test_locate_against_tagged_pool(oracle_mod):
+    cfg = small_cfg("fp32", n_sessions=3, prefix_dist=("uniform", 3, 23))
+    sess = W.make_sessions(cfg, 4)
+    k_pool, v_pool = tagged_pools(cfg)
+    buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    rng = np.random.default_rng(0)
+    ls, bst = cfg.layer_elems, cfg.block_elems
+    for _ in range(200):
+        s = int(rng.integers(sess.n_sessions))
+        t = int(rng.integers(sess.prefix_lens[s]))
+        layer, kv = int(rng.integers(cfg.n_layers)), int(rng.integers(2))
+        pe, be = oracle_mod.kv_locate(ls, bst, cfg.n_layers, cfg.block_size, cfg.n_kv_heads, cfg.head_dim,
+                                      sess.block_table, sess.prefix_lens, sess.buf_token_offsets, s, layer, kv, t)
+        pool = (v_pool if kv else k_pool).ravel()
+        assert np.array_equal(pool[pe: pe + cfg.row_elems].view(np.uint32), buf[be: be + cfg.row_elems].view(np.uint32))
+        kvd, l, b, o, g, c = decode_tag(pool[pe: pe + 1].view(np.uint32), cfg)
+        assert (kvd[0], l[0], b[0], o[0], g[0], c[0]) == (kv, layer, sess.block_table[s, t // cfg.block_size],
+                                                          t % cfg.block_size, 0, 0)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_unpack_round_trips_and_leaves_other_bytes_alone(oracle_mod, dtype):
+    cfg = small_cfg(dtype, n_sessions=6, n_layers=2, n_blocks=96, prefix_dist=("geometric", 9.0, 1, 29))
+    sess = W.make_sessions(cfg, 21)
+    assert np.all(sess.prefix_lens % cfg.block_size != 0)       # every last block partial
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 8)
+    buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+
+    # (a) same table: the pool does not change
+    k2, v2 = k_pool.copy(), v_pool.copy()
+    oracle_mod.kv_unpack(k2, v2, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, buf)
+    assert k2.tobytes() == k_pool.tobytes() and v2.tobytes() == v_pool.tobytes()
+
+    # (b) fresh table into a sentinel pool: packing again gives the same buffer ...
+    ks = np.empty_like(k_pool); vs = np.empty_like(v_pool)
+    sent = 0x7FC1 if dtype == "bf16" else 0x7FC00001
+    uview = (lambda a: a) if dtype == "bf16" else (lambda a: a.view(np.uint32))
+    uview(ks)[...] = sent; uview(vs)[...] = sent
+    oracle_mod.kv_unpack(ks, vs, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, buf)
+    again = oracle_mod.kv_pack(ks, vs, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert again.tobytes() == buf.tobytes()
+    # ... and exactly the valid token slots were written, nothing else
+    written = np.zeros(ks.shape[:3], dtype=bool)      # [L][block][slot]
+    for s in range(sess.n_sessions):
+        for t in range(int(sess.prefix_lens[s])):
+            written[:, sess.dst_block_table[s, t // cfg.block_size], t % cfg.block_size] = True
+    for pool in (ks, vs):
+        is_sent = np.all(uview(pool) == sent, axis=(3, 4))
+        assert np.array_equal(is_sent, ~written)
+    # and each written slot holds the source token's row
+    for s in range(sess.n_sessions):
+        for t in range(int(sess.prefix_lens[s])):
+            j, o = t // cfg.block_size, t % cfg.block_size
+            assert np.array_equal(ks[:, sess.dst_block_table[s, j], o], k_pool[:, sess.block_table[s, j], o])
+            assert np.array_equal(vs[:, sess.dst_block_table[s, j], o], v_pool[:, sess.block_table[s, j], o])
+
+
+def test_pack_preserves_nan_payloads_and_negative_zero(oracle_mod):
+    cfg = small_cfg("bf16", n_sessions=2, n_layers=1, n_blocks=16, prefix_dist=("const", 7))
+    sess = W.make_sessions(cfg, 5)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 5, kind="counter")    # raw bit patterns: NaNs, infs, -0 included
+    k_pool[0, sess.block_table[0, 0], 0, 0, :4] = [0x8000, 0x7FC1, 0xFFFF, 0x7F80]
+    buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert list(buf[:4]) == [0x8000, 0x7FC1, 0xFFFF, 0x7F80]
+
+
+def test_buffer_bytes_match_the_papers_cache_sizes(oracle_mod):
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "kv_cache_sizes.txt")) if ln.strip() and ln[0] != "#"]
+    assert len(rows) == 2
+    for L, H, d, e, tokens, paper_gb in rows:
+        got = oracle_mod.kv_buffer_bytes(int(L), int(H), int(d), int(e), int(tokens))
+        assert got == int(paper_gb) * 2 ** 30                 # the paper's figure, read as binary gigabytes
+        assert abs(got / 1e9 - float(paper_gb)) / float(paper_gb) < 0.08   # and within rounding of decimal GB
+    # empty sessions occupy nothing
+    assert oracle_mod.kv_buffer_bytes(32, 8, 128, 2, 0) == 0
+
+
+def test_pack_empty_and_zero_length_sessions(oracle_mod):
+    cfg = small_cfg("bf16", n_sessions=3, prefix_dist=("const", 0))
+    sess = W.make_sessions(cfg, 1)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 1)
+    buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert buf.size == 0
+
+
+# --------------------------------------------------------------------------------------------------------
+# attention
+# --------------------------------------------------------------------------------------------------------
+def run_oracle_attn(oracle_mod, sess, inputs, **kw):
+    k_pool, v_pool, q, k_new, v_new = inputs
+    return oracle_mod.prefix_prefill_attn(k_pool, v_pool, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                          sess.block_table, sess.cfg.scale, **kw)
+
+
+@pytest.mark.parametrize("dtype,seed", [("bf16", 1), ("bf16", 2), ("fp32", 3), ("fp32", 4)])
+def test_attention_brute_force_full_matrix(oracle_mod, dtype, seed):
+    cfg = small_cfg(dtype, n_sessions=4, prefix_dist=("uniform", 0, 21), new_dist=("uniform", 0, 9),
+                    n_q_heads=6, n_kv_heads=2)
+    sess = W.make_sessions(cfg, seed)
+    inputs = W.make_attn_inputs(cfg, sess, seed)
+    got = run_oracle_attn(oracle_mod, sess, inputs)
+    ref = brute_force_attention(*inputs, sess, cfg.scale)
+    assert got.shape == ref.shape
+    if got.size:
+        assert np.max(np.abs(got - ref)) < 1e-12
+
+
+@pytest.mark.parametrize("G", [1, 4])
+def test_attention_matches_torch_sdpa_fp64(oracle_mod, G):
+    import torch
+    import torch.nn.functional as F
+    cfg = small_cfg("bf16", n_sessions=3, n_q_heads=2 * G, n_kv_heads=2, head_dim=16, block_size=16, n_blocks=32,
+                    prefix_dist=("uniform", 5, 70), new_dist=("uniform", 1, 12), scale=0.25)
+    sess = W.make_sessions(cfg, 17)
+    inputs = W.make_attn_inputs(cfg, sess, 17)
+    k_pool, v_pool, q, k_new, v_new = inputs
+    got = run_oracle_attn(oracle_mod, sess, inputs)
+    for s in range(sess.n_sessions):
+        P, N = int(sess.prefix_lens[s]), int(sess.new_lens[s])
+        a, b = int(sess.cu_new_lens[s]), int(sess.cu_new_lens[s + 1])
+        K = torch.from_numpy(contiguous_kv(k_pool, sess.block_table[s], P, k_new[a:b])).permute(1, 0, 2)  # [H_kv][n][d]
+        V = torch.from_numpy(contiguous_kv(v_pool, sess.block_table[s], P, v_new[a:b])).permute(1, 0, 2)
+        Q = torch.from_numpy(to_f64(q[a:b])).permute(1, 0, 2)                                            # [H_q][N][d]
+        K = K.repeat_interleave(G, dim=0)
+        V = V.repeat_interleave(G, dim=0)
+        mask = torch.ones(N, P + N, dtype=torch.bool).tril(diagonal=P)
+        ref = F.scaled_dot_product_attention(Q[None], K[None], V[None], attn_mask=mask[None, None], scale=0.25)[0]
+        assert torch.max(torch.abs(torch.from_numpy(got[a:b]).permute(1, 0, 2) - ref)).item() < 1e-12
+
+
+def test_cached_prefix_equals_full_recompute_and_any_split(oracle_mod):
+    """Resuming from a cached prefix must give the rows a full recompute of the session gives (Sec. 3.5:
+    the mechanism changes neither model nor data)."""
+    cfg = small_cfg("bf16", n_sessions=1, prefix_dist=("const", 37), new_dist=("const", 11), n_blocks=64)
+    sess = W.make_sessions(cfg, 2)
+    inputs = W.make_attn_inputs(cfg, sess, 2)
+    k_pool, v_pool, q, k_new, v_new = inputs
+    ref = run_oracle_attn(oracle_mod, sess, inputs)
+    P, N = 37, 11
+    kfull = np.stack([k_pool[sess.block_table[0, t // 4], t % 4] for t in range(P)] + list(k_new))
+    vfull = np.stack([v_pool[sess.block_table[0, t // 4], t % 4] for t in range(P)] + list(v_new))
+    for split in (0, 5, 36, 40):          # tokens [0, split) cached, the rest "new"
+        c2 = small_cfg("bf16", n_sessions=1, prefix_dist=("const", split), new_dist=("const", P + N - split),
+                       n_blocks=64)
+        s2 = W.make_sessions(c2, 99)      # a different random table
+        kp = np.full_like(k_pool, W.SENTINEL16); vp = np.full_like(v_pool, W.SENTINEL16)
+        for t in range(split):
+            kp[s2.block_table[0, t // 4], t % 4] = kfull[t]
+            vp[s2.block_table[0, t // 4], t % 4] = vfull[t]
+        n2 = P + N - split
+        q2 = np.zeros((n2,) + q.shape[1:], dtype=q.dtype)
+        keep = min(N, n2)                                 # earlier rows: zero queries, discarded below
+        q2[n2 - keep:] = q[N - keep:]
+        out = oracle_mod.prefix_prefill_attn(kp, vp, q2, np.ascontiguousarray(kfull[split:]),
+                                             np.ascontiguousarray(vfull[split:]), s2.cu_new_lens, s2.prefix_lens,
+                                             s2.block_table, cfg.scale)
+        assert np.max(np.abs(out[n2 - keep:] - ref[N - keep:])) < 1e-13
+
+
+def test_block_id_permutation_leaves_output_unchanged(oracle_mod):
+    cfg = small_cfg("fp32", n_sessions=3, prefix_dist=("uniform", 4, 30), new_dist=("uniform", 1, 6), n_blocks=48)
+    sess = W.make_sessions(cfg, 6)
+    inputs = W.make_attn_inputs(cfg, sess, 6)
+    ref = run_oracle_attn(oracle_mod, sess, inputs)
+    perm = np.random.default_rng(0).permutation(cfg.n_blocks).astype(np.int32)    # old id -> new id
+    k_pool, v_pool, q, k_new, v_new = inputs
+    kp = np.empty_like(k_pool); vp = np.empty_like(v_pool)
+    kp[perm] = k_pool; vp[perm] = v_pool
+    tab = np.where(sess.block_table >= 0, perm[np.maximum(sess.block_table, 0)], -1).astype(np.int32)
+    out = oracle_mod.prefix_prefill_attn(kp, vp, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens, tab, cfg.scale)
+    assert np.array_equal(out, ref)
+
+
+def test_softmax_weights_sum_to_one_and_are_causal(oracle_mod):
+    cfg = small_cfg("bf16", n_sessions=2, prefix_dist=("uniform", 10, 40), new_dist=("const", 5), n_blocks=64)
+    sess = W.make_sessions(cfg, 8)
+    inputs = W.make_attn_inputs(cfg, sess, 8)
+    full = run_oracle_attn(oracle_mod, sess, inputs)
+    for s in range(2):
+        for i in range(5):
+            for h in range(cfg.n_q_heads):
+                w, o = oracle_mod.attn_row_weights(*inputs, sess.cu_new_lens, sess.prefix_lens, sess.block_table,
+                                                   cfg.scale, s, i, h)
+                assert w.size == sess.prefix_lens[s] + i + 1      # sees the prefix and new tokens 0..i, no more
+                assert abs(w.sum() - 1.0) < 1e-12 and np.all(w > 0)
+                assert np.array_equal(o, full[sess.cu_new_lens[s] + i, h])
+
+
+def test_attention_closed_forms(oracle_mod):
+    cfg = small_cfg("fp32", n_sessions=1, prefix_dist=("const", 13), new_dist=("const", 4), n_blocks=16)
+    sess = W.make_sessions(cfg, 10)
+    k_pool, v_pool, q, k_new, v_new = W.make_attn_inputs(cfg, sess, 10)
+    ids = sess.block_table[0, :4]
+    P, N, G = 13, 4, cfg.group
+
+    # (1) all keys equal -> uniform weights -> output = mean of the visible V rows
+    kp = k_pool.copy(); kp[ids] = 0.5
+    kn = np.full_like(k_new, 0.5)
+    out = oracle_mod.prefix_prefill_attn(kp, v_pool, q, kn, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                         sess.block_table, cfg.scale)
+    vfull = np.concatenate([v_pool[ids].reshape(-1, cfg.n_kv_heads, cfg.head_dim)[:P], v_new]).astype(np.float64)
+    for i in range(N):
+        for h in range(cfg.n_q_heads):
+            assert np.allclose(out[i, h], vfull[: P + i + 1, h // G].mean(axis=0), rtol=0, atol=1e-13)
+
+    # (2) V constant per kv-head -> output is that constant, whatever the scores
+    vp = v_pool.copy(); vn = v_new.copy()
+    for g in range(cfg.n_kv_heads):
+        vp[ids, :, g] = 3.0 + g
+        vn[:, g] = 3.0 + g
+    out = oracle_mod.prefix_prefill_attn(k_pool, vp, q, k_new, vn, sess.cu_new_lens, sess.prefix_lens,
+                                         sess.block_table, cfg.scale)
+    for h in range(cfg.n_q_heads):
+        assert np.allclose(out[:, h], 3.0 + h // G, rtol=0, atol=1e-13)
+
+    # (3) one key dominates: q = e_0, key j* = 1000 e_0, all other keys 0  ->  output = V[j*]
+    qq = np.zeros_like(q); qq[..., 0] = 1.0
+    kp = k_pool.copy(); kp[ids] = 0.0
+    kn = np.zeros_like(k_new)
+    jstar = 6
+    kp[ids[jstar // 4], jstar % 4, :, 0] = 1000.0
+    out = oracle_mod.prefix_prefill_attn(kp, v_pool, qq, kn, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                         sess.block_table, 1.0)
+    for h in range(cfg.n_q_heads):
+        assert np.allclose(out[:, h], vfull[jstar, h // G][None], rtol=0, atol=1e-13)
+
+    # (4) the scale is applied to the scores: doubling the scale == doubling q
+    a = oracle_mod.prefix_prefill_attn(k_pool, v_pool, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                       sess.block_table, 2 * cfg.scale)
+    b = oracle_mod.prefix_prefill_attn(k_pool, v_pool, 2 * q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                       sess.block_table, cfg.scale)
+    assert np.max(np.abs(a - b)) < 1e-12
+
+
+def test_first_turn_single_token_returns_its_own_value(oracle_mod):
+    cfg = small_cfg("bf16", n_sessions=2, prefix_dist=("const", 0), new_dist=("const", 1))
+    sess = W.make_sessions(cfg, 12)
+    k_pool, v_pool, q, k_new, v_new = W.make_attn_inputs(cfg, sess, 12)
+    out = oracle_mod.prefix_prefill_attn(k_pool, v_pool, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                         sess.block_table, cfg.scale)
+    for h in range(cfg.n_q_heads):
+        assert np.array_equal(out[:, h], to_f64(v_new)[:, h // cfg.group])
+
+
+def test_token_subset_matches_full(oracle_mod):
+    cfg = small_cfg("bf16", n_sessions=3, prefix_dist=("uniform", 1, 19), new_dist=("uniform", 1, 7))
+    sess = W.make_sessions(cfg, 14)
+    inputs = W.make_attn_inputs(cfg, sess, 14)
+    full = run_oracle_attn(oracle_mod, sess, inputs)
+    rows = [0, sess.total_new_tokens - 1, sess.total_new_tokens // 2]
+    part = run_oracle_attn(oracle_mod, sess, inputs, token_subset=rows)
+    assert np.array_equal(part[rows], full[rows])
+    others = np.setdiff1d(np.arange(sess.total_new_tokens), rows)
+    assert np.all(np.isnan(part[others]))

@@ -1,0 +1,136 @@
+"""Session lengths and block tables for a workload config (host, numpy, seeded)."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from .configs import WorkloadConfig
+
+
+@dataclass
+class SessionBatch:
+    cfg: WorkloadConfig
+    prefix_lens: np.ndarray          # int32 [S]   cached tokens per session
+    new_lens: np.ndarray             # int32 [S]   tokens of the new turn
+    block_table: np.ndarray          # int32 [S, table_stride]   physical block ids, -1 beyond the session's blocks
+    dst_block_table: Optional[np.ndarray]  # int32 [S, table_stride]  a disjoint "free list" assignment, or None
+    buf_token_offsets: np.ndarray    # int64 [S+1]  exclusive prefix sum of prefix_lens
+    cu_new_lens: np.ndarray          # int32 [S+1]  exclusive prefix sum of new_lens
+
+    @property
+    def n_sessions(self) -> int:
+        return int(self.prefix_lens.shape[0])
+
+    @property
+    def table_stride(self) -> int:
+        return int(self.block_table.shape[1])
+
+    @property
+    def total_prefix_tokens(self) -> int:
+        return int(self.buf_token_offsets[-1])
+
+    @property
+    def total_new_tokens(self) -> int:
+        return int(self.cu_new_lens[-1])
+
+    @property
+    def max_prefix_len(self) -> int:
+        return int(self.prefix_lens.max()) if self.n_sessions else 0
+
+    @property
+    def max_new_len(self) -> int:
+        return int(self.new_lens.max()) if self.n_sessions else 0
+
+    def blocks_per_session(self) -> np.ndarray:
+        bs = self.cfg.block_size
+        return (self.prefix_lens.astype(np.int64) + bs - 1) // bs
+
+    def owned_blocks(self, dst: bool = False) -> np.ndarray:
+        """All physical block ids listed for valid tokens (source or destination table), flattened."""
+        tab = self.dst_block_table if dst else self.block_table
+        nb = self.blocks_per_session()
+        return np.concatenate([tab[s, : nb[s]] for s in range(self.n_sessions)]) if self.n_sessions else \
+            np.zeros(0, np.int32)
+
+    def payload_bytes(self) -> int:
+        """Bytes of the migration buffer: K and V of every layer for every cached token."""
+        return self.total_prefix_tokens * self.cfg.kv_bytes_per_token()
+
+    def attn_flops(self) -> float:
+        """4 * H_q * d * sum_s N_s * (P_s + (N_s + 1) / 2): QK^T and PV over the visible region only."""
+        n = self.new_lens.astype(np.float64)
+        p = self.prefix_lens.astype(np.float64)
+        return float(4.0 * self.cfg.n_q_heads * self.cfg.head_dim * np.sum(n * (p + (n + 1.0) / 2.0)))
+
+    def attn_bytes(self) -> int:
+        """One pass over the cached K,V of one layer plus Q, O, K_new, V_new."""
+        c = self.cfg
+        kv = self.total_prefix_tokens * 2 * c.row_elems * c.elem_bytes
+        qo = self.total_new_tokens * (2 * c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * c.elem_bytes
+        return int(kv + qo)
+
+
+def _draw_lengths(dist, n, rng: np.random.Generator, block_size: int) -> np.ndarray:
+    kind = dist[0]
+    if kind == "const":
+        return np.full(n, dist[1], dtype=np.int32)
+    if kind == "uniform":
+        return rng.integers(dist[1], dist[2] + 1, size=n).astype(np.int32)
+    if kind == "geometric":
+        _, mean, lo, hi = dist
+        p = np.clip(rng.geometric(1.0 / mean, size=n), lo, hi).astype(np.int64)
+        # every last block partially filled
+        full = (p % block_size) == 0
+        p = np.where(full, np.where(p >= hi, p - 1, p + 1), p)
+        return p.astype(np.int32)
+    if kind == "lognormal":
+        _, median, sigma, lo, hi = dist
+        v = np.rint(np.exp(rng.normal(np.log(median), sigma, size=n)))
+        return np.clip(v, lo, hi).astype(np.int32)
+    if kind == "mixed":
+        _, n_decode, median, sigma, lo, hi = dist
+        n_decode = min(n_decode, n)
+        out = np.ones(n, dtype=np.int32)
+        order = rng.permutation(n)
+        prefill_rows = np.sort(order[n_decode:])
+        v = np.rint(np.exp(rng.normal(np.log(median), sigma, size=prefill_rows.shape[0])))
+        out[prefill_rows] = np.clip(v, lo, hi).astype(np.int32)
+        return out
+    raise ValueError(f"unknown length distribution {kind!r}")
+
+
+def make_sessions(cfg: WorkloadConfig, seed: Optional[int] = None) -> SessionBatch:
+    """Draw lengths, then hand every session consecutive slices of one seeded permutation of the pool.
+
+    A session's blocks are therefore a uniform sample without replacement of the whole pool, listed in
+    random order (fragmented); the destination table (the "fresh free list") takes the next slices of
+    the same permutation, so it shares no block with any source table.
+    """
+    rng = np.random.default_rng(cfg.seed if seed is None else seed)
+    S, bs = cfg.n_sessions, cfg.block_size
+    prefix = _draw_lengths(cfg.prefix_dist, S, rng, bs)
+    new = _draw_lengths(cfg.new_dist, S, rng, bs)
+    nblk = (prefix.astype(np.int64) + bs - 1) // bs
+    total_blk = int(nblk.sum())
+    need = total_blk * (2 if cfg.fresh_tables else 1)
+    if need > cfg.n_blocks:
+        raise ValueError(f"{cfg.name}: {need} blocks needed, pool has {cfg.n_blocks}")
+    perm = rng.permutation(cfg.n_blocks).astype(np.int32)
+    stride = max(1, int(nblk.max()) if S else 1)
+    table = np.full((S, stride), -1, dtype=np.int32)
+    dst = np.full((S, stride), -1, dtype=np.int32) if cfg.fresh_tables else None
+    at = 0
+    for s in range(S):
+        table[s, : nblk[s]] = perm[at: at + nblk[s]]
+        at += int(nblk[s])
+    if dst is not None:
+        for s in range(S):
+            dst[s, : nblk[s]] = perm[at: at + nblk[s]]
+            at += int(nblk[s])
+    off = np.zeros(S + 1, dtype=np.int64)
+    off[1:] = np.cumsum(prefix.astype(np.int64))
+    cu = np.zeros(S + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(new.astype(np.int64)).astype(np.int32)
+    return SessionBatch(cfg, prefix, new, table, dst, off, cu)
