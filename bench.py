@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the turn-resumption hot path on one MI355X.
+
+One step = one pass over one synthetic batch, inputs resident in HBM:
+    symph_kv_pack (all layers, every session)  ->  symph_kv_unpack (into fresh free-list blocks)
+    ->  symph_prefix_prefill_attn (one layer, ragged batch).
+Host staging (device <-> pinned host on a side stream) is PCIe-bound and is timed on its own, outside the step.
+
+Prints ONE JSON line.  `value` is the step's algorithmic HBM traffic divided by the step time; the per-kernel
+figures (GB/s against the 8 TB/s HBM peak for pack / unpack, TFLOP/s against the 2.5 PFLOP/s dense bf16 MFMA peak
+for attention) are carried next to it, each measured with events on the launch stream inside the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="llama8b", help="workload name (default: the config the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-staging", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the CPU-baseline leg")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, sess, budget_s: float):
+    """Time the oracle, as it stands, on a bounded sample of the same workload on the host cores."""
+    import oracle
+    import workloads as W
+    oracle.build()
+    threads = oracle.num_threads()
+    # migration sample: same shapes and length recipe, fewer layers and sessions, small pool
+    mcfg = W.scaled_config(cfg, n_layers=min(cfg.n_layers, 4), n_sessions=min(cfg.n_sessions, 4), n_blocks=4096)
+    msess = W.make_sessions(mcfg)
+    shape = (mcfg.n_layers, mcfg.n_blocks, mcfg.block_size, mcfg.n_kv_heads, mcfg.head_dim)
+    dt = np.uint16 if cfg.dtype == "bf16" else np.float32
+    kp = np.arange(int(np.prod(shape)), dtype=np.uint32).astype(dt).reshape(shape)
+    vp = kp[::-1].copy()
+    t0 = time.perf_counter()
+    buf = oracle.kv_pack(kp, vp, msess.block_table, msess.prefix_lens, msess.buf_token_offsets)
+    t1 = time.perf_counter()
+    oracle.kv_unpack(kp, vp, msess.dst_block_table, msess.prefix_lens, msess.buf_token_offsets, buf)
+    t2 = time.perf_counter()
+    mig_bytes = 2.0 * msess.payload_bytes()          # read + write
+    pack_gbs = mig_bytes / (t1 - t0) / 1e9
+    unpack_gbs = mig_bytes / (t2 - t1) / 1e9
+    # attention sample: rows of the real batch, sized from a probe so the leg stays near the budget
+    inputs = W.make_attn_inputs(cfg, sess)
+    rng = np.random.default_rng(0)
+    T = sess.total_new_tokens
+    order = rng.permutation(T)
+    keys_per_tok = np.repeat(sess.prefix_lens.astype(np.float64), sess.new_lens) + \
+        np.concatenate([np.arange(1, n + 1) for n in sess.new_lens]).astype(np.float64)
+    flops_tok = 4.0 * cfg.n_q_heads * cfg.head_dim * keys_per_tok
+    probe = order[:4]
+    t0 = time.perf_counter()
+    oracle.prefix_prefill_attn(*inputs, sess.cu_new_lens, sess.prefix_lens, sess.block_table, cfg.scale,
+                               token_subset=probe)
+    rate = flops_tok[probe].sum() / (time.perf_counter() - t0)
+    n_rows = int(np.clip(budget_s * 0.7 * rate / max(flops_tok.mean(), 1.0), 8, T))
+    rows = order[:n_rows]
+    t0 = time.perf_counter()
+    oracle.prefix_prefill_attn(*inputs, sess.cu_new_lens, sess.prefix_lens, sess.block_table, cfg.scale,
+                               token_subset=rows)
+    attn_s = time.perf_counter() - t0
+    attn_gflops = flops_tok[rows].sum() / attn_s / 1e9
+    # the whole step on the CPU, extrapolated from the three sampled rates, in the unit of `value`
+    full_mig = 2.0 * sess.payload_bytes()
+    step_s = full_mig / (pack_gbs * 1e9) + full_mig / (unpack_gbs * 1e9) + sess.attn_flops() / (attn_gflops * 1e9)
+    step_bytes = 2.0 * full_mig + sess.attn_bytes()
+    return {
+        "value": step_bytes / step_s / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": (f"pack+unpack of {msess.n_sessions} sessions x {mcfg.n_layers} layers "
+                   f"({msess.payload_bytes() / 1e6:.0f} MB payload, same shapes and length recipe); attention on "
+                   f"{n_rows} of {T} query tokens of the real batch (all heads); step extrapolated from the three rates"),
+        "pack_GBps": pack_gbs, "unpack_GBps": unpack_gbs, "attn_fp64_GFLOPs": attn_gflops,
+        "extrapolated_step_ms": step_s * 1e3,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (sessions shard across GPUs with no exchange step; "
+              "no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2412_16434_amd as S
+    import workloads as W
+
+    S.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = W.get_config(args.config)
+    if cfg.dtype != "bf16":
+        print("bench.py: benchmark configs are bf16", file=sys.stderr)
+        sys.exit(2)
+    sess = W.make_sessions(cfg)
+
+    # ---- inputs, resident in HBM before anything is timed ------------------------------------------------
+    L, nb, bs = cfg.n_layers, cfg.n_blocks, cfg.block_size
+    shape = (L, nb, bs, cfg.n_kv_heads, cfg.head_dim)
+    k_pool = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    v_pool = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    sent = int(np.array([W.SENTINEL16], dtype=np.uint16).view(np.int16)[0])
+    k_pool.view(torch.int16).fill_(sent)
+    v_pool.view(torch.int16).fill_(sent)
+    W.fill_pool_blocks_device(k_pool, v_pool, cfg, sess.owned_blocks())
+    # the attention layer holds the seeded Gaussian draws (owned blocks only)
+    kh, vh, qh, knh, vnh = W.make_attn_inputs(cfg, sess)
+    la = cfg.attn_layer
+    owned = torch.from_numpy(sess.owned_blocks().astype(np.int64)).to(dev)
+    for pool, host in ((k_pool, kh), (v_pool, vh)):
+        src = torch.from_numpy(host.view(np.int16)[sess.owned_blocks()]).to(dev)
+        pool[la].view(torch.int16).index_copy_(0, owned, src)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    q, k_new, v_new = to_dev(qh), to_dev(knh), to_dev(vnh)
+    out = torch.empty_like(q)
+    table = torch.from_numpy(sess.block_table).to(dev)
+    dst_table = torch.from_numpy(sess.dst_block_table).to(dev)
+    prefix_lens = torch.from_numpy(sess.prefix_lens).to(dev)
+    offsets = torch.from_numpy(sess.buf_token_offsets).to(dev)
+    cu = torch.from_numpy(sess.cu_new_lens).to(dev)
+    cache = S.KVCache(k_pool, v_pool)
+    total = sess.total_prefix_tokens
+    payload = S.kv_buffer_bytes(cache, total)
+    assert payload == sess.payload_bytes()
+    buf = torch.empty(payload // 2, dtype=torch.bfloat16, device=dev)
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
+                                                     sess.max_new_len, sess.max_prefix_len)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def step(evs=None):
+        if evs: evs[0].record()
+        S.kv_pack(cache, table, prefix_lens, offsets, total, buf)
+        if evs: evs[1].record()
+        S.kv_unpack(cache, dst_table, prefix_lens, offsets, total, buf)
+        if evs: evs[2].record()
+        S.prefix_prefill_attn(cache, la, q, k_new, v_new, out, cu, prefix_lens, table, sess.max_new_len,
+                              sess.max_prefix_len, cfg.scale, workspace=ws if ws_bytes else None)
+        if evs: evs[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    pack_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    unpack_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+
+    # ---- contiguous copy of the same byte count: the practical HBM ceiling -------------------------------
+    scratch = torch.empty_like(buf)
+    for _ in range(2):
+        S.device_copy(scratch, buf, payload)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        S.device_copy(scratch, buf, payload)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ms = e0.elapsed_time(e1) / 5
+    del scratch
+
+    # ---- host staging on a side stream (PCIe) -----------------------------------------------------------------
+    staging = None
+    if not args.no_staging:
+        nbytes = min(payload, 1 << 30)
+        host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        side = torch.cuda.Stream()
+        main_stream = torch.cuda.current_stream()
+        ev = torch.cuda.Event()
+        bview = buf.view(torch.uint8)
+        res = {}
+        for name, fn in (("d2h", lambda: S.stage_to_host(host, bview, nbytes, main_stream, side, ev)),
+                         ("h2d", lambda: S.stage_to_device(bview, host, nbytes, main_stream, side, ev))):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            res[name + "_GBps"] = 3 * nbytes / (time.perf_counter() - t0) / 1e9
+        res["bytes"] = nbytes
+        staging = res
+        del host
+
+    mig_bytes = 2.0 * payload                 # every payload byte read once and written once
+    attn_flops = sess.attn_flops()
+    attn_bytes = sess.attn_bytes()
+    step_bytes = 2.0 * mig_bytes + attn_bytes
+    pack_gbs = mig_bytes / pack_ms / 1e6
+    unpack_gbs = mig_bytes / unpack_ms / 1e6
+    attn_tflops = attn_flops / attn_ms / 1e9
+    dominant = "pack" if pack_ms >= unpack_ms else "unpack"
+    dom_gbs = pack_gbs if dominant == "pack" else unpack_gbs
+
+    result = {
+        "metric": "prefix-prefill attn TFLOP/s + KV pack/unpack GB/s, as % of MI355X peaks",
+        "value": step_bytes / ms_step / 1e6,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_sessions": sess.n_sessions, "n_layers": L, "n_q_heads": cfg.n_q_heads,
+                   "n_kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "block_size": bs, "pool_blocks": nb,
+                   "prefix_tokens": total, "new_tokens": sess.total_new_tokens, "payload_bytes": payload,
+                   "step": "kv_pack(all layers) + kv_unpack(all layers) + prefix_prefill_attn(one layer)"},
+        "kv_pack": {"ms": pack_ms, "GBps": pack_gbs, "pct_hbm_peak": 100 * pack_gbs / HBM_PEAK_GBS},
+        "kv_unpack": {"ms": unpack_ms, "GBps": unpack_gbs, "pct_hbm_peak": 100 * unpack_gbs / HBM_PEAK_GBS},
+        "prefix_prefill_attn": {"ms": attn_ms, "TFLOPs": attn_tflops,
+                                "pct_mfma_bf16_peak": 100 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                                "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops},
+        "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
+        "host_staging": staging,
+        "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None},
+        "roofline_attn": {"kernel": "attn_mfma", "bound": "mfma", "achieved": attn_tflops,
+                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                          "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, sess, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,151 @@
+/*
+ * symph.h - C ABI of the MI355X (gfx950) turn-resumption library.
+ *
+ * The operations behind resuming a conversation turn in Symphony (arxiv 2412.16434): a session's K,V cache is
+ * moved between GPUs / memory tiers ahead of the next request (Sec. 3.2 "Symphony Node Manager", Sec. 3.3
+ * "Hierarchical memory management", "cooperative memory management"), and the new turn then attends to that
+ * cached prefix instead of recomputing it (Sec. 2.1 attention definition and "KV Cache", Sec. 2.4 swap vs.
+ * recompute).
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers; everything else is passed by value.
+ *   - The caller owns every buffer.  The library allocates no memory and keeps no state between calls; calls may
+ *     be issued concurrently on different streams as long as the memory they write does not overlap.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work and return
+ *     without synchronising; device arrays must stay valid until the stream has executed the work.
+ *   - Return value: SYMPH_OK or a negative symph_status.  Nothing aborts or throws across the ABI.  Host-visible
+ *     arguments are validated before anything is launched.  Contents of device arrays (block ids, lengths) are
+ *     the caller's contract; kernels additionally skip any block id outside [0, n_blocks) and any token beyond
+ *     the buffer instead of touching memory out of range.
+ *
+ * Layouts ("element" = one value of cache dtype: bf16 = 2 bytes, fp32 = 4 bytes)
+ *   paged cache   K pool and V pool.  Element (layer l, block b, slot o, kv-head g, dim c) of K lives at
+ *                 k_base + l*layer_stride + b*block_stride + (o*n_kv_heads + g)*head_dim + c   (elements),
+ *                 same for V from v_base.  A block holds block_size consecutive tokens of one session.
+ *   block table   int32 [n_sessions][table_stride]; token t of session s is in block table[s][t / block_size],
+ *                 slot t % block_size.  Entries past ceil(P_s / block_size) are ignored.
+ *   migration buffer   session-major, then layer, then K before V, then token, head, dim; exactly P_s tokens
+ *                 per session, no padding.  Row (s, l, kv, t) starts at element
+ *                 (off[s]*2*L + (2*l + kv)*P_s + t) * n_kv_heads*head_dim,  off = exclusive prefix sum of P.
+ *                 Layer l of a session is thus one contiguous chunk that can be shipped or consumed first
+ *                 (Sec. 3.3: layer-wise asynchronous reads/writes, lower layers first).
+ *   q, out        [T][n_q_heads][head_dim];  k_new, v_new  [T][n_kv_heads][head_dim];  T = sum of new-turn
+ *                 lengths; session s owns rows cu_new_lens[s] .. cu_new_lens[s+1]-1.
+ */
+#ifndef SYMPH_H_
+#define SYMPH_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SYMPH_OK = 0,
+  SYMPH_EINVAL = -1,       /* null pointer, non-positive shape, inconsistent sizes, bad scale */
+  SYMPH_EUNSUPPORTED = -2, /* shape / dtype / alignment the kernels do not cover */
+  SYMPH_ELAUNCH = -3,      /* the HIP runtime refused the launch or copy */
+  SYMPH_EWORKSPACE = -4    /* workspace or buffer smaller than required */
+} symph_status;
+
+typedef enum { SYMPH_BF16 = 0, SYMPH_FP32 = 1 } symph_dtype;
+
+/* A paged K,V cache owned by the caller (device memory). Strides are in elements. */
+typedef struct {
+  void* k_base;          /* device: K pool, layer 0, block 0 */
+  void* v_base;          /* device: V pool, layer 0, block 0 */
+  int64_t layer_stride;  /* elements between consecutive layers of one pool */
+  int64_t block_stride;  /* elements between consecutive blocks; >= block_size*n_kv_heads*head_dim */
+  int32_t n_layers;
+  int32_t n_blocks;      /* blocks per layer pool; block ids are 0 .. n_blocks-1 */
+  int32_t block_size;    /* tokens per block */
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t dtype;         /* symph_dtype */
+} symph_kv_cache;
+
+/* Bytes of the migration buffer for total_tokens cached tokens: total_tokens * 2 * L * n_kv_heads * head_dim *
+ * elem_bytes.  (Llama-3.1-70B shape at 32768 tokens gives 10 GiB, the figure in Sec. 1.)  Negative on bad input. */
+int64_t symph_kv_buffer_bytes(const symph_kv_cache* cache, int64_t total_tokens);
+
+/*
+ * Gather: copy the cached K,V of every listed session, all layers, out of its scattered blocks into the
+ * migration buffer (Sec. 3.2: the node manager serves K,V fetch requests from peers and moves caches between
+ * tiers; Sec. 3.5: data is not changed - the copy is bit-exact).
+ *   d_block_table [n_sessions][table_stride] int32, d_prefix_lens [n_sessions] int32,
+ *   d_buf_token_offsets [n_sessions+1] int64 (exclusive prefix sum of prefix lengths),
+ *   total_tokens = host copy of d_buf_token_offsets[n_sessions] (sizes the grid without a device read-back),
+ *   d_buf: device, buf_bytes >= symph_kv_buffer_bytes(cache, total_tokens), 16-byte aligned.
+ * Reads only slots of valid tokens (never the unused tail of a partially filled last block); a block id may
+ * appear in several sessions.  n_sessions == 0 or total_tokens == 0 is SYMPH_OK with no launch.
+ * Needs row bytes (n_kv_heads*head_dim*elem) to be a multiple of 4 and strides/pointers aligned to
+ * min(16, largest power of two dividing the row bytes).
+ */
+int32_t symph_kv_pack(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
+                      const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets, int32_t n_sessions,
+                      int64_t total_tokens, void* d_buf, int64_t buf_bytes, void* stream);
+
+/*
+ * Scatter: the inverse of symph_kv_pack through a destination block table taken from the free list (Sec. 3.3:
+ * the node manager greedily fills free GPU memory with arriving caches; Sec. 3.4 cases 1-3).  Writes only the
+ * slots of valid tokens; every other byte of the pools is left untouched.  A block id listed twice in the
+ * destination table has two writers and the result for that block is undefined.
+ */
+int32_t symph_kv_unpack(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,
+                        const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets, int32_t n_sessions,
+                        int64_t total_tokens, const void* d_buf, int64_t buf_bytes, void* stream);
+
+/*
+ * Prefix-cached prefill attention for one layer (Sec. 2.1: A_h = softmax(Q_h K_h^T * scale), y = concat_h A_h V_h;
+ * "KV Cache": a token attends to all prior tokens).  For session s, query head h, new token i:
+ *   out[cu[s]+i][h][:] = sum_j softmax_j(scale * <q, k_j>) v_j,   j over the P_s cached keys (paged, kv-head
+ *   h / (n_q_heads / n_kv_heads)) followed by new keys 0..i of k_new / v_new (causal, self included).
+ * The new turn's K,V are NOT yet in the paged cache; they are passed as k_new / v_new.
+ *   layer: which layer of `cache` holds the prefix.  q/k_new/v_new/out have the cache dtype.
+ *   d_cu_new_lens [n_sessions+1] int32, d_prefix_lens [n_sessions] int32, d_block_table as above.
+ *   total_new_tokens = T, max_new_len >= max N_s, max_prefix_len >= max P_s (host copies, to size grids).
+ *   scale > 0 and finite (fp32).  d_workspace: device scratch of at least
+ *   symph_prefix_prefill_attn_workspace_bytes(...) bytes, 256-byte aligned (may be NULL when that is 0).
+ * Arithmetic: bf16 inputs, fp32 accumulation on MFMA, fp32 online softmax, probabilities rounded to bf16 before
+ * the P*V product, output rounded to nearest even; fp32 inputs are computed in fp32 throughout.
+ * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads.  Sessions with N_s == 0 produce no rows;
+ * P_s == 0 is a plain causal prefill.
+ */
+int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
+                                  const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
+                                  const int32_t* d_prefix_lens, const int32_t* d_block_table, int32_t table_stride,
+                                  int32_t n_sessions, int32_t n_q_heads, int32_t total_new_tokens,
+                                  int32_t max_new_len, int32_t max_prefix_len, float scale, void* d_workspace,
+                                  int64_t workspace_bytes, void* stream);
+
+/* Scratch bytes symph_prefix_prefill_attn needs for these host-side bounds (0 is possible). Negative on bad input. */
+int64_t symph_prefix_prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
+                                                  int32_t total_new_tokens, int32_t max_new_len,
+                                                  int32_t max_prefix_len);
+
+/*
+ * Host staging on a side stream (Sec. 2.4 "Swap": K,V swapped to host memory; Sec. 3.3: asynchronous reads and
+ * writes so transfers overlap inference).  symph_stage_to_host orders a device->host copy of `bytes` bytes
+ * after everything already enqueued on `producer_stream` (typically the pack) and runs it on `side_stream`;
+ * symph_stage_to_device runs a host->device copy on `side_stream` and makes `consumer_stream` (typically the
+ * unpack) wait for it.  h_pinned must be pinned host memory (hipHostMalloc) for the copy to be asynchronous.
+ * `event` is a caller-created hipEvent_t (as void*) used for the ordering; it may be reused once the streams
+ * have passed it.  side_stream must differ from the other stream.
+ */
+int32_t symph_stage_to_host(void* h_pinned, const void* d_buf, int64_t bytes, void* producer_stream,
+                            void* side_stream, void* event);
+int32_t symph_stage_to_device(void* d_buf, const void* h_pinned, int64_t bytes, void* consumer_stream,
+                              void* side_stream, void* event);
+
+/* Plain contiguous device copy with the same 16-byte-per-lane access shape as pack / unpack: the practical
+ * HBM ceiling the migration kernels are compared with, and the known-size kernel used to calibrate hardware
+ * traffic counters.  bytes must be a multiple of 16, pointers 16-byte aligned. */
+int32_t symph_device_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
+
+const char* symph_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYMPH_H_ */

@@ -1,0 +1,22 @@
+"""MI355X-native turn-resumption kernels (K,V pack / unpack, prefix-cached prefill attention).
+
+A thin binding over the C-ABI library ``libsymph.so`` (see ``include/symph.h``): argument marshalling only,
+every step of the path runs in the HIP kernels.  Importing this package does not touch the GPU; the library
+is loaded on first use and a missing library is an error, never a fallback.
+"""
+from .binding import (  # noqa: F401
+    KVCache,
+    SymphError,
+    lib_path,
+    load_library,
+    kv_buffer_bytes,
+    kv_pack,
+    kv_unpack,
+    prefix_prefill_attn,
+    prefix_prefill_attn_workspace_bytes,
+    stage_to_host,
+    stage_to_device,
+    device_copy,
+    status_string,
+    EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,189 @@
+"""ctypes binding of libsymph.so: same names as the C entry points, torch tensors in, status checked."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsymph.so")
+_lib = None
+
+SYMPH_BF16, SYMPH_FP32 = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_prefix_prefill_attn",
+    "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host", "symph_stage_to_device",
+    "symph_device_copy", "symph_status_string",
+)
+
+
+class SymphError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class _CacheStruct(C.Structure):
+    _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("layer_stride", C.c_int64),
+                ("block_stride", C.c_int64), ("n_layers", C.c_int32), ("n_blocks", C.c_int32),
+                ("block_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsymph.so (built in-tree by ``paper_2412_16434_amd/build.py``). Raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2412_16434_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(_LIB_PATH)
+    i32, i64, vp, f32 = C.c_int32, C.c_int64, C.c_void_p, C.c_float
+    cp = C.POINTER(_CacheStruct)
+    lib.symph_kv_buffer_bytes.restype = i64
+    lib.symph_kv_buffer_bytes.argtypes = [cp, i64]
+    for fn in (lib.symph_kv_pack, lib.symph_kv_unpack):
+        fn.restype = i32
+        fn.argtypes = [cp, vp, i32, vp, vp, i32, i64, vp, i64, vp]
+    lib.symph_prefix_prefill_attn.restype = i32
+    lib.symph_prefix_prefill_attn.argtypes = [cp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32,
+                                              vp, i64, vp]
+    lib.symph_prefix_prefill_attn_workspace_bytes.restype = i64
+    lib.symph_prefix_prefill_attn_workspace_bytes.argtypes = [cp, i32, i32, i32, i32, i32]
+    for fn in (lib.symph_stage_to_host, lib.symph_stage_to_device):
+        fn.restype = i32
+        fn.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.symph_device_copy.restype = i32
+    lib.symph_device_copy.argtypes = [vp, vp, i64, vp]
+    lib.symph_status_string.restype = C.c_char_p
+    lib.symph_status_string.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().symph_status_string(int(status)).decode()
+
+
+@dataclass
+class KVCache:
+    """A paged K,V cache in device memory: two torch tensors ``[L][n_blocks][bs][H_kv][d]`` (bf16 or fp32)."""
+    k_pool: "object"
+    v_pool: "object"
+
+    def __post_init__(self):
+        import torch
+        k, v = self.k_pool, self.v_pool
+        if k.dim() != 5 or k.shape != v.shape or k.dtype != v.dtype:
+            raise ValueError("pools must be two [L][n_blocks][bs][H_kv][d] tensors of one dtype")
+        if k.dtype not in (torch.bfloat16, torch.float32):
+            raise ValueError("cache dtype must be bfloat16 or float32")
+        if k.stride()[2:] != (k.shape[3] * k.shape[4], k.shape[4], 1) or v.stride() != k.stride():
+            raise ValueError("token, head and dim axes must be dense")
+
+    @property
+    def dtype_code(self) -> int:
+        import torch
+        return SYMPH_BF16 if self.k_pool.dtype == torch.bfloat16 else SYMPH_FP32
+
+    def struct(self) -> _CacheStruct:
+        k = self.k_pool
+        return _CacheStruct(k.data_ptr(), self.v_pool.data_ptr(), k.stride(0), k.stride(1), k.shape[0], k.shape[1],
+                            k.shape[2], k.shape[3], k.shape[4], self.dtype_code)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _event_ptr(event) -> int:
+    """hipEvent_t of a torch.cuda.Event (torch creates the handle on the first record)."""
+    if isinstance(event, int):
+        return event
+    if not event.cuda_event:
+        event.record()
+    return event.cuda_event
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SymphError(status, where)
+
+
+def kv_buffer_bytes(cache: KVCache, total_tokens: int) -> int:
+    st = cache.struct()
+    n = load_library().symph_kv_buffer_bytes(C.byref(st), int(total_tokens))
+    if n < 0:
+        raise SymphError(-1, "symph_kv_buffer_bytes")
+    return int(n)
+
+
+def kv_pack(cache: KVCache, block_table, prefix_lens, buf_token_offsets, total_tokens: int, buf, stream=None) -> None:
+    """Gather into ``buf`` (any dtype, 1-D device tensor of at least kv_buffer_bytes bytes)."""
+    st = cache.struct()
+    _check(load_library().symph_kv_pack(C.byref(st), _ptr(block_table), block_table.shape[1] if block_table.dim() == 2
+                                        else 0, _ptr(prefix_lens), _ptr(buf_token_offsets), prefix_lens.shape[0],
+                                        int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(),
+                                        _stream_ptr(stream)), "symph_kv_pack")
+
+
+def kv_unpack(cache: KVCache, dst_block_table, prefix_lens, buf_token_offsets, total_tokens: int, buf,
+              stream=None) -> None:
+    st = cache.struct()
+    _check(load_library().symph_kv_unpack(C.byref(st), _ptr(dst_block_table), dst_block_table.shape[1]
+                                          if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens),
+                                          _ptr(buf_token_offsets), prefix_lens.shape[0], int(total_tokens), _ptr(buf),
+                                          buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_unpack")
+
+
+def prefix_prefill_attn_workspace_bytes(cache: KVCache, n_sessions: int, n_q_heads: int, total_new_tokens: int,
+                                        max_new_len: int, max_prefix_len: int) -> int:
+    st = cache.struct()
+    n = load_library().symph_prefix_prefill_attn_workspace_bytes(C.byref(st), n_sessions, n_q_heads, total_new_tokens,
+                                                                 max_new_len, max_prefix_len)
+    if n < 0:
+        raise SymphError(-1, "symph_prefix_prefill_attn_workspace_bytes")
+    return int(n)
+
+
+def prefix_prefill_attn(cache: KVCache, layer: int, q, k_new, v_new, out, cu_new_lens, prefix_lens, block_table,
+                        max_new_len: int, max_prefix_len: int, scale: float, workspace=None, stream=None) -> None:
+    """out[T][H_q][d] <- attention of the new turn over [cached prefix ; causal new tokens] for one layer."""
+    st = cache.struct()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().symph_prefix_prefill_attn(
+        C.byref(st), int(layer), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(cu_new_lens), _ptr(prefix_lens),
+        _ptr(block_table), block_table.shape[1] if block_table is not None and block_table.dim() == 2 else 0,
+        prefix_lens.shape[0], q.shape[1], q.shape[0], int(max_new_len), int(max_prefix_len), float(scale),
+        _ptr(workspace), ws_bytes, _stream_ptr(stream)), "symph_prefix_prefill_attn")
+
+
+def stage_to_host(h_pinned, d_buf, nbytes: int, producer_stream, side_stream, event) -> None:
+    _check(load_library().symph_stage_to_host(_ptr(h_pinned), _ptr(d_buf), int(nbytes), _stream_ptr(producer_stream),
+                                              _stream_ptr(side_stream), _event_ptr(event)), "symph_stage_to_host")
+
+
+def stage_to_device(d_buf, h_pinned, nbytes: int, consumer_stream, side_stream, event) -> None:
+    _check(load_library().symph_stage_to_device(_ptr(d_buf), _ptr(h_pinned), int(nbytes),
+                                                _stream_ptr(consumer_stream), _stream_ptr(side_stream),
+                                                _event_ptr(event)), "symph_stage_to_device")
+
+
+def device_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(load_library().symph_device_copy(_ptr(dst), _ptr(src), int(nbytes), _stream_ptr(stream)),
+           "symph_device_copy")

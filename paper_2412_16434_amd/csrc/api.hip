@@ -1,0 +1,164 @@
+// extern "C" entry points: host-side validation, then launches. No allocation, no global state.
+#include "common.h"
+
+namespace symph {
+
+int32_t validate_cache(const symph_kv_cache* c) {
+  if (!c) return SYMPH_EINVAL;
+  if (!c->k_base || !c->v_base) return SYMPH_EINVAL;
+  if (c->n_layers <= 0 || c->n_blocks <= 0 || c->block_size <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0)
+    return SYMPH_EINVAL;
+  if (elem_bytes_of(c->dtype) == 0) return SYMPH_EUNSUPPORTED;
+  const int64_t block_elems = (int64_t)c->block_size * c->n_kv_heads * c->head_dim;
+  if (c->block_stride < block_elems) return SYMPH_EINVAL;
+  if (c->n_layers > 1 && c->layer_stride <= 0) return SYMPH_EINVAL;
+  return SYMPH_OK;
+}
+
+static int32_t migrate(bool pack, const symph_kv_cache* cache, const int32_t* d_table, int32_t table_stride,
+                       const int32_t* d_prefix_lens, const int64_t* d_offsets, int32_t n_sessions,
+                       int64_t total_tokens, void* d_buf, int64_t buf_bytes, void* stream) {
+  int32_t rc = validate_cache(cache);
+  if (rc != SYMPH_OK) return rc;
+  if (n_sessions < 0 || total_tokens < 0 || table_stride < 0 || buf_bytes < 0) return SYMPH_EINVAL;
+  if (n_sessions == 0 || total_tokens == 0) return SYMPH_OK;
+  if (!d_table || !d_prefix_lens || !d_offsets || !d_buf || table_stride == 0) return SYMPH_EINVAL;
+  const int64_t need = symph_kv_buffer_bytes(cache, total_tokens);
+  if (need < 0) return SYMPH_EINVAL;
+  if (buf_bytes < need) return SYMPH_EWORKSPACE;
+  return launch_kv_migrate(pack, cache, d_table, table_stride, d_prefix_lens, d_offsets, n_sessions, total_tokens,
+                           d_buf, buf_bytes, (hipStream_t)stream);
+}
+
+}  // namespace symph
+
+using namespace symph;
+
+extern "C" {
+
+int64_t symph_kv_buffer_bytes(const symph_kv_cache* cache, int64_t total_tokens) {
+  if (!cache || total_tokens < 0) return -1;
+  const int eb = elem_bytes_of(cache->dtype);
+  if (eb == 0 || cache->n_layers <= 0 || cache->n_kv_heads <= 0 || cache->head_dim <= 0) return -1;
+  return total_tokens * 2 * (int64_t)cache->n_layers * cache->n_kv_heads * cache->head_dim * eb;
+}
+
+int32_t symph_kv_pack(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
+                      const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets, int32_t n_sessions,
+                      int64_t total_tokens, void* d_buf, int64_t buf_bytes, void* stream) {
+  return migrate(true, cache, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets, n_sessions,
+                 total_tokens, d_buf, buf_bytes, stream);
+}
+
+int32_t symph_kv_unpack(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,
+                        const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets, int32_t n_sessions,
+                        int64_t total_tokens, const void* d_buf, int64_t buf_bytes, void* stream) {
+  return migrate(false, cache, d_dst_block_table, table_stride, d_prefix_lens, d_buf_token_offsets, n_sessions,
+                 total_tokens, const_cast<void*>(d_buf), buf_bytes, stream);
+}
+
+int64_t symph_prefix_prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
+                                                  int32_t total_new_tokens, int32_t max_new_len,
+                                                  int32_t max_prefix_len) {
+  if (!cache || n_sessions < 0 || n_q_heads <= 0 || total_new_tokens < 0 || max_new_len < 0 || max_prefix_len < 0)
+    return -1;
+  return prefill_attn_workspace_bytes(cache, n_sessions, n_q_heads, total_new_tokens, max_new_len, max_prefix_len);
+}
+
+int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
+                                  const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
+                                  const int32_t* d_prefix_lens, const int32_t* d_block_table, int32_t table_stride,
+                                  int32_t n_sessions, int32_t n_q_heads, int32_t total_new_tokens,
+                                  int32_t max_new_len, int32_t max_prefix_len, float scale, void* d_workspace,
+                                  int64_t workspace_bytes, void* stream) {
+  int32_t rc = validate_cache(cache);
+  if (rc != SYMPH_OK) return rc;
+  if (layer < 0 || layer >= cache->n_layers) return SYMPH_EINVAL;
+  if (n_sessions < 0 || total_new_tokens < 0 || max_new_len < 0 || max_prefix_len < 0 || table_stride < 0 ||
+      workspace_bytes < 0)
+    return SYMPH_EINVAL;
+  if (n_q_heads <= 0 || n_q_heads % cache->n_kv_heads != 0) return SYMPH_EINVAL;
+  if (!(scale > 0.0f) || !(scale < INFINITY)) return SYMPH_EINVAL;
+  if (max_new_len > total_new_tokens) return SYMPH_EINVAL;
+  if (n_sessions == 0 || total_new_tokens == 0) return SYMPH_OK;
+  if (!d_q || !d_k_new || !d_v_new || !d_out || !d_cu_new_lens || !d_prefix_lens) return SYMPH_EINVAL;
+  if (max_prefix_len > 0 && (!d_block_table || table_stride == 0)) return SYMPH_EINVAL;
+  if (max_prefix_len > 0 && (int64_t)table_stride * cache->block_size < max_prefix_len) return SYMPH_EINVAL;
+  if (cache->head_dim != 64 && cache->head_dim != 128) return SYMPH_EUNSUPPORTED;
+  const int64_t need = prefill_attn_workspace_bytes(cache, n_sessions, n_q_heads, total_new_tokens, max_new_len,
+                                                    max_prefix_len);
+  if (need > 0 && (!d_workspace || workspace_bytes < need)) return SYMPH_EWORKSPACE;
+
+  const int eb = elem_bytes_of(cache->dtype);
+  AttnArgs a;
+  a.k_layer = (const char*)cache->k_base + (int64_t)layer * cache->layer_stride * eb;
+  a.v_layer = (const char*)cache->v_base + (int64_t)layer * cache->layer_stride * eb;
+  a.block_stride = cache->block_stride;
+  a.n_blocks = cache->n_blocks;
+  a.block_size = cache->block_size;
+  a.n_kv_heads = cache->n_kv_heads;
+  a.n_q_heads = n_q_heads;
+  a.head_dim = cache->head_dim;
+  a.dtype = cache->dtype;
+  a.q = d_q;
+  a.k_new = d_k_new;
+  a.v_new = d_v_new;
+  a.out = d_out;
+  a.cu_new_lens = d_cu_new_lens;
+  a.prefix_lens = d_prefix_lens;
+  a.table = d_block_table;
+  a.table_stride = table_stride;
+  a.n_sessions = n_sessions;
+  a.total_new_tokens = total_new_tokens;
+  a.max_new_len = max_new_len;
+  a.max_prefix_len = max_prefix_len;
+  a.scale = scale;
+  a.workspace = d_workspace;
+  a.workspace_bytes = workspace_bytes;
+  return launch_prefill_attn(a, (hipStream_t)stream);
+}
+
+int32_t symph_stage_to_host(void* h_pinned, const void* d_buf, int64_t bytes, void* producer_stream,
+                            void* side_stream, void* event) {
+  if (bytes < 0) return SYMPH_EINVAL;
+  if (bytes == 0) return SYMPH_OK;
+  if (!h_pinned || !d_buf || !event || side_stream == producer_stream) return SYMPH_EINVAL;
+  if (hipEventRecord((hipEvent_t)event, (hipStream_t)producer_stream) != hipSuccess) return SYMPH_ELAUNCH;
+  if (hipStreamWaitEvent((hipStream_t)side_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
+  if (hipMemcpyAsync(h_pinned, d_buf, (size_t)bytes, hipMemcpyDeviceToHost, (hipStream_t)side_stream) != hipSuccess)
+    return SYMPH_ELAUNCH;
+  return SYMPH_OK;
+}
+
+int32_t symph_stage_to_device(void* d_buf, const void* h_pinned, int64_t bytes, void* consumer_stream,
+                              void* side_stream, void* event) {
+  if (bytes < 0) return SYMPH_EINVAL;
+  if (bytes == 0) return SYMPH_OK;
+  if (!h_pinned || !d_buf || !event || side_stream == consumer_stream) return SYMPH_EINVAL;
+  if (hipMemcpyAsync(d_buf, h_pinned, (size_t)bytes, hipMemcpyHostToDevice, (hipStream_t)side_stream) != hipSuccess)
+    return SYMPH_ELAUNCH;
+  if (hipEventRecord((hipEvent_t)event, (hipStream_t)side_stream) != hipSuccess) return SYMPH_ELAUNCH;
+  if (hipStreamWaitEvent((hipStream_t)consumer_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
+  return SYMPH_OK;
+}
+
+int32_t symph_device_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream) {
+  if (bytes < 0) return SYMPH_EINVAL;
+  if (bytes == 0) return SYMPH_OK;
+  if (!d_dst || !d_src) return SYMPH_EINVAL;
+  if ((bytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15)) return SYMPH_EUNSUPPORTED;
+  return launch_device_copy(d_dst, d_src, bytes, (hipStream_t)stream);
+}
+
+const char* symph_status_string(int32_t status) {
+  switch (status) {
+    case SYMPH_OK: return "ok";
+    case SYMPH_EINVAL: return "invalid argument";
+    case SYMPH_EUNSUPPORTED: return "unsupported shape, dtype or alignment";
+    case SYMPH_ELAUNCH: return "HIP launch or copy failed";
+    case SYMPH_EWORKSPACE: return "buffer or workspace too small";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

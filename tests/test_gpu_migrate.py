@@ -1,0 +1,273 @@
+"""symph_kv_pack / symph_kv_unpack against the CPU oracle: bit-exact, element by element on scaled-down versions
+of the five workloads and on edge cases; sampled rows plus whole-pool properties at the full sizes."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_16434_amd as S
+import workloads as W
+from gpu_util import DEV, DeviceSessions, gpu_pack, gpu_unpack, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def sentinel_like(a: np.ndarray) -> np.ndarray:
+    out = np.empty_like(a)
+    if a.dtype == np.uint16:
+        out[...] = W.SENTINEL16
+    else:
+        out.view(np.uint32)[...] = W.values.SENTINEL32
+    return out
+
+
+def run_case(oracle_mod, cfg, seed=None):
+    """pack == oracle; unpack into a sentinel pool == oracle's pool, every byte; round trips."""
+    sess = W.make_sessions(cfg, seed)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, seed)
+    ref_buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    buf = gpu_pack(cache, ds)
+    torch.cuda.synchronize()
+    got = to_host(buf)
+    assert got.tobytes() == ref_buf.tobytes(), "pack differs from the oracle"
+    # pack must not write to the pools
+    assert to_host(cache.k_pool).tobytes() == k_pool.tobytes() and to_host(cache.v_pool).tobytes() == v_pool.tobytes()
+
+    # unpack through the destination table into sentinel pools, oracle and GPU side by side
+    ks, vs = sentinel_like(k_pool), sentinel_like(v_pool)
+    oracle_mod.kv_unpack(ks, vs, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, ref_buf)
+    dcache = S.KVCache(to_dev(sentinel_like(k_pool)), to_dev(sentinel_like(v_pool)))
+    gpu_unpack(dcache, ds, buf, dst=True)
+    torch.cuda.synchronize()
+    assert to_host(dcache.k_pool).tobytes() == ks.tobytes(), "unpack: K pool differs from the oracle"
+    assert to_host(dcache.v_pool).tobytes() == vs.tobytes(), "unpack: V pool differs from the oracle"
+    # resume test: packing what was unpacked gives the buffer back
+    again = gpu_pack(dcache, ds, dst=True)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16) if again.dtype == torch.bfloat16 else again,
+                       buf.view(torch.int16) if buf.dtype == torch.bfloat16 else buf)
+    return sess
+
+
+SCALED = {
+    "tiny_fp32": dict(),
+    "llama8b": dict(n_layers=3, n_sessions=5, prefix_scale=0.05, new_scale=0.2, n_blocks=512),
+    "llama70b_long": dict(n_layers=5, prefix_scale=1 / 64, new_scale=1 / 8, n_blocks=128),
+    "many_short": dict(n_layers=2, n_sessions=40, prefix_scale=0.1, n_blocks=1024),
+    "mixed_resume_incoming": dict(n_layers=4, n_sessions=3, prefix_scale=1 / 16, n_blocks=128),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SCALED))
+def test_pack_unpack_scaled_configs(oracle_mod, name):
+    cfg = W.get_config(name)
+    if SCALED[name]:
+        cfg = W.scaled_config(cfg, **SCALED[name])
+    run_case(oracle_mod, cfg)
+
+
+def _cfg(**kw):
+    base = dict(name="edge", index=20, dtype="bf16", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=64, block_size=16,
+                n_blocks=64, n_sessions=4, prefix_dist=("uniform", 1, 100), new_dist=("const", 1), sigma=1.0, scale=0.1)
+    base.update(kw)
+    return W.WorkloadConfig(**base)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(prefix_dist=("const", 1)),                                   # one token per session
+    dict(prefix_dist=("const", 16), n_sessions=3),                    # exactly one full block
+    dict(prefix_dist=("const", 17), n_sessions=3),                    # one full block + one slot
+    dict(prefix_dist=("uniform", 0, 40), n_sessions=9),               # zero-length sessions mixed in
+    dict(n_layers=1, n_sessions=1, prefix_dist=("const", 500), n_blocks=80),
+    dict(n_layers=7, block_size=8, n_blocks=256, prefix_dist=("uniform", 1, 60)),   # odd layer count, other block size
+    dict(n_layers=3, n_kv_heads=1, head_dim=64, block_size=32, n_blocks=64, prefix_dist=("uniform", 1, 200)),
+    dict(dtype="fp32", n_kv_heads=3, head_dim=20, block_size=4, n_blocks=128, prefix_dist=("uniform", 1, 50)),  # 240 B rows
+    dict(dtype="bf16", n_kv_heads=1, head_dim=6, block_size=4, n_blocks=128, prefix_dist=("uniform", 1, 50)),   # 12 B rows: 4-byte path
+])
+def test_pack_unpack_edge_cases(oracle_mod, kw):
+    run_case(oracle_mod, _cfg(**kw), seed=77)
+
+
+def test_all_sessions_empty_is_a_no_op(oracle_mod):
+    cfg = _cfg(prefix_dist=("const", 0))
+    sess = W.make_sessions(cfg, 1)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 1)
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    buf = torch.zeros(16, dtype=torch.bfloat16, device=DEV)
+    S.kv_pack(cache, ds.table, ds.prefix_lens, ds.offsets, 0, buf)
+    S.kv_unpack(cache, ds.table, ds.prefix_lens, ds.offsets, 0, buf)
+    torch.cuda.synchronize()
+    assert not buf.any() and to_host(cache.k_pool).tobytes() == k_pool.tobytes()
+
+
+def test_invalid_block_ids_are_skipped_not_dereferenced(oracle_mod):
+    """Ids outside [0, n_blocks) must not be touched: the rows they name stay as they were in the buffer."""
+    cfg = _cfg(n_sessions=2, prefix_dist=("const", 40))
+    sess = W.make_sessions(cfg, 3)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 3)
+    ref = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    bad = sess.block_table.copy()
+    bad[1, 1] = cfg.n_blocks + 5
+    bad[0, 2] = -3
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    ds = DeviceSessions(sess)
+    ds.table = torch.from_numpy(bad).to(DEV)
+    buf = torch.full((ref.size,), -1, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    S.kv_pack(cache, ds.table, ds.prefix_lens, ds.offsets, sess.total_prefix_tokens, buf)
+    torch.cuda.synchronize()
+    got = to_host(buf)
+    row = cfg.row_elems
+    for s in range(2):
+        for layer in range(cfg.n_layers):
+            for kv in range(2):
+                for t in range(40):
+                    _, be = oracle_mod.kv_locate(cfg.layer_elems, cfg.block_elems, cfg.n_layers, 16, cfg.n_kv_heads,
+                                                 cfg.head_dim, sess.block_table, sess.prefix_lens,
+                                                 sess.buf_token_offsets, s, layer, kv, t)
+                    skipped = (s == 1 and t // 16 == 1) or (s == 0 and t // 16 == 2)
+                    expect = np.full(row, 0xFFFF, np.uint16) if skipped else ref[be: be + row]
+                    assert np.array_equal(got[be: be + row], expect)
+
+
+def test_strided_cache_layout(oracle_mod):
+    """Block-major allocation [n_blocks][L][2][bs][H][d] described through the stride fields."""
+    cfg = _cfg(n_layers=3, n_sessions=3, prefix_dist=("uniform", 5, 90))
+    sess = W.make_sessions(cfg, 9)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 9)          # [L][nb][bs][H][d]
+    ref = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    fused = np.stack([k_pool, v_pool], axis=0).transpose(2, 1, 0, 3, 4, 5).copy()     # [nb][L][2][bs][H][d]
+    ft = to_dev(fused)
+    kview = ft[:, :, 0].permute(1, 0, 2, 3, 4)               # [L][nb][bs][H][d] view with strides
+    vview = ft[:, :, 1].permute(1, 0, 2, 3, 4)
+    cache = S.KVCache(kview, vview)
+    ds = DeviceSessions(sess)
+    buf = gpu_pack(cache, ds)
+    torch.cuda.synchronize()
+    assert to_host(buf).tobytes() == ref.tobytes()
+
+
+def test_pack_on_side_stream_and_host_staging(oracle_mod):
+    """a4: pack on one stream, device->pinned-host copy ordered after it on a side stream, and back."""
+    cfg = W.scaled_config(W.get_config("llama8b"), n_layers=4, n_sessions=6, prefix_scale=0.1, n_blocks=1024)
+    sess = W.make_sessions(cfg)
+    k_pool, v_pool = W.make_pool_host(cfg, sess)
+    ref = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    ev = torch.cuda.Event()
+    nbytes = ref.nbytes
+    host = torch.empty(ref.size, dtype=torch.int16, pin_memory=True)
+    torch.cuda.synchronize()
+    buf = gpu_pack(cache, ds, stream=main)
+    S.stage_to_host(host, buf, nbytes, main, side, ev)
+    side.synchronize()
+    assert host.numpy().view(np.uint16).tobytes() == ref.tobytes()
+    # and back: host -> device on the side stream, unpack waits for it on the main stream
+    dcache = S.KVCache(to_dev(sentinel_like(k_pool)), to_dev(sentinel_like(v_pool)))
+    buf2 = torch.zeros_like(buf)
+    torch.cuda.synchronize()
+    ev2 = torch.cuda.Event()
+    S.stage_to_device(buf2, host, nbytes, main, side, ev2)
+    gpu_unpack(dcache, ds, buf2, dst=True, stream=main)
+    torch.cuda.synchronize()
+    ks, vs = sentinel_like(k_pool), sentinel_like(v_pool)
+    oracle_mod.kv_unpack(ks, vs, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, ref)
+    assert to_host(dcache.k_pool).tobytes() == ks.tobytes() and to_host(dcache.v_pool).tobytes() == vs.tobytes()
+
+
+def test_device_copy_matches_source():
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 22,), dtype=torch.int32, device=DEV)
+    for n_bytes in (16, 4096, (1 << 24) - 16, 1 << 24):
+        dst = torch.zeros_like(src)
+        S.device_copy(dst, src, n_bytes)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[: n_bytes // 4], src[: n_bytes // 4]) and not dst[n_bytes // 4:].any()
+
+
+# ---------------------------------------------------------------------------------------------------------
+# full sizes: counter-filled device pools, sampled rows against the oracle's index map, whole-pool properties
+# ---------------------------------------------------------------------------------------------------------
+def _full_size_case(oracle_mod, cfg, n_sample=20000):
+    sess = W.make_sessions(cfg)
+    L, nb, bs = cfg.n_layers, cfg.n_blocks, cfg.block_size
+    shape = (L, nb, bs, cfg.n_kv_heads, cfg.head_dim)
+    k_pool = torch.empty(shape, dtype=torch.bfloat16, device=DEV)
+    v_pool = torch.empty(shape, dtype=torch.bfloat16, device=DEV)
+    sent = np.array([W.SENTINEL16], dtype=np.uint16).view(np.int16)[0]
+    k_pool.view(torch.int16).fill_(int(sent))
+    v_pool.view(torch.int16).fill_(int(sent))
+    src_blocks = sess.owned_blocks()
+    W.fill_pool_blocks_device(k_pool, v_pool, cfg, src_blocks)
+    cache = S.KVCache(k_pool, v_pool)
+    ds = DeviceSessions(sess)
+    buf = gpu_pack(cache, ds)
+    torch.cuda.synchronize()
+    assert buf.numel() * 2 == sess.payload_bytes()
+
+    # (1) sampled rows: the oracle's index map says where a row comes from and where it goes
+    rng = np.random.default_rng(5)
+    row = cfg.row_elems
+    ss = rng.integers(0, sess.n_sessions, n_sample)
+    ts = (rng.random(n_sample) * sess.prefix_lens[ss]).astype(np.int64)
+    ts[: sess.n_sessions] = sess.prefix_lens - 1                 # every session's last token (partial block)
+    ss[: sess.n_sessions] = np.arange(sess.n_sessions)
+    ls = rng.integers(0, L, n_sample)
+    kvs = rng.integers(0, 2, n_sample)
+    pe = np.empty(n_sample, np.int64); be = np.empty(n_sample, np.int64)
+    pe_dst = np.empty(n_sample, np.int64)
+    for i in range(n_sample):
+        pe[i], be[i] = oracle_mod.kv_locate(cfg.layer_elems, cfg.block_elems, L, bs, cfg.n_kv_heads, cfg.head_dim,
+                                            sess.block_table, sess.prefix_lens, sess.buf_token_offsets,
+                                            int(ss[i]), int(ls[i]), int(kvs[i]), int(ts[i]))
+        pe_dst[i], _ = oracle_mod.kv_locate(cfg.layer_elems, cfg.block_elems, L, bs, cfg.n_kv_heads, cfg.head_dim,
+                                            sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets,
+                                            int(ss[i]), int(ls[i]), int(kvs[i]), int(ts[i]))
+    cols = np.arange(row, dtype=np.int64)
+    expect = np.where(kvs[:, None] == 0, W.counter_bits_host(cfg.seed, 0, pe[:, None] + cols),
+                      W.counter_bits_host(cfg.seed, 1, pe[:, None] + cols))
+    idx = torch.from_numpy(be[:, None] + cols).to(DEV)
+    got = buf.view(torch.int16)[idx].cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, expect), "pack: sampled rows differ"
+
+    # (2) unpack into the fresh destination blocks of the same pool
+    gpu_unpack(cache, ds, buf, dst=True)
+    torch.cuda.synchronize()
+    kflat, vflat = k_pool.view(torch.int16).view(-1), v_pool.view(torch.int16).view(-1)
+    idx = torch.from_numpy(pe_dst[:, None] + cols).to(DEV)
+    got_k = kflat[idx].cpu().numpy().view(np.uint16)
+    got_v = vflat[idx].cpu().numpy().view(np.uint16)
+    assert np.array_equal(np.where(kvs[:, None] == 0, got_k, got_v), expect), "unpack: sampled rows differ"
+
+    # (3) whole pool: exactly the source and destination blocks hold data, everything else is still sentinel,
+    #     and the unused tail slots of every destination last block are still sentinel
+    dst_blocks = sess.owned_blocks(dst=True)
+    owned = np.zeros(nb, dtype=bool)
+    owned[src_blocks] = True
+    owned[dst_blocks] = True
+    owned_t = torch.from_numpy(owned).to(DEV)
+    for pool in (k_pool, v_pool):
+        for layer in range(L):
+            touched = (pool[layer].view(torch.int16).view(nb, -1) != int(sent)).any(dim=1)
+            assert torch.equal(touched, owned_t), f"layer {layer}: blocks written outside the tables"
+    nblk = sess.blocks_per_session()
+    for s in range(sess.n_sessions):
+        tail = int(sess.prefix_lens[s]) % bs
+        if tail:
+            last = int(sess.dst_block_table[s, nblk[s] - 1])
+            for pool in (k_pool, v_pool):
+                assert bool((pool[:, last, tail:].view(torch.int16) == int(sent)).all())
+
+    # (4) resume: packing from the destination table gives the identical buffer
+    again = gpu_pack(cache, ds, dst=True)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), buf.view(torch.int16))
+
+
+@pytest.mark.parametrize("name", ["llama8b", "llama70b_long", "many_short", "mixed_resume_incoming"])
+def test_pack_unpack_full_size(oracle_mod, name):
+    _full_size_case(oracle_mod, W.get_config(name))
+    torch.cuda.empty_cache()
