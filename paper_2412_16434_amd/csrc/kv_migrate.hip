@@ -22,7 +22,9 @@ struct MigrateParams {
   int64_t block_stride_b;  // bytes
   int32_t row_bytes;
   int32_t vecs_per_row;
+  int32_t row_shift;  // log2(vecs_per_row) when it is a power of two, else -1
   int32_t block_size;
+  int32_t bs_shift;   // log2(block_size) when it is a power of two, else -1
   int32_t n_blocks;
   int32_t n_planes;  // 2 * n_layers
   const int32_t* table;
@@ -51,12 +53,23 @@ __device__ __forceinline__ void store_vec(char* p, VecT v) {
     *reinterpret_cast<VecT*>(p) = v;
 }
 
-template <typename VecT, bool PACK, int PLANES, bool NT>
+// UNIFORM: a token row is a whole number of waves (vecs_per_row is a power of two >= 64), so the token index, the
+// session search and the block-table read are wave-uniform and run once per wave on the scalar unit.
+template <typename VecT, bool PACK, int PLANES, bool NT, bool UNIFORM>
 __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) {
   const int64_t gv = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t tg = gv / p.vecs_per_row;  // token in the concatenated token space of all sessions
+  int64_t tg;  // token in the concatenated token space of all sessions
+  int32_t col;
+  if constexpr (UNIFORM) {
+    const int64_t t64 = gv >> p.row_shift;
+    col = (int32_t)gv & (p.vecs_per_row - 1);
+    tg = ((int64_t)__builtin_amdgcn_readfirstlane((int32_t)(t64 >> 32)) << 32) |
+         (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)t64);
+  } else {
+    tg = p.row_shift >= 0 ? (gv >> p.row_shift) : gv / p.vecs_per_row;
+    col = (int32_t)(gv - tg * p.vecs_per_row);
+  }
   if (tg >= p.total_tokens) return;
-  const int32_t col = (int32_t)(gv - tg * p.vecs_per_row);
 
   // session s with offsets[s] <= tg < offsets[s+1] (sessions of length 0 are skipped by taking the last match)
   int32_t lo = 0, hi = p.n_sessions;
@@ -70,51 +83,59 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   const int32_t s = lo;
   const int64_t off_s = p.offsets[s];
   const int32_t P = p.prefix_lens[s];
-  const int64_t t = tg - off_s;
-  if (t >= P) return;  // inconsistent offsets / lengths: touch nothing
-  const int32_t j = (int32_t)(t / p.block_size);
+  const int64_t t64 = tg - off_s;
+  if (t64 >= P) return;  // inconsistent offsets / lengths: touch nothing
+  const int32_t t = (int32_t)t64;
+  const int32_t j = p.bs_shift >= 0 ? (t >> p.bs_shift) : t / p.block_size;
   if (j >= p.table_stride) return;
   const int32_t b = p.table[(int64_t)s * p.table_stride + j];
   if (b < 0 || b >= p.n_blocks) return;  // not a block of this cache: touch nothing
-  const int32_t slot = (int32_t)(t - (int64_t)j * p.block_size);
+  const int32_t slot = t - j * p.block_size;
+  const int64_t plane_b = (int64_t)P * p.row_bytes;  // one (layer, K|V) plane of this session in the buffer
+  const int64_t sess_b = off_s * p.n_planes * p.row_bytes;
+  if (sess_b + plane_b * p.n_planes > p.buf_bytes) return;  // the session would not fit the buffer: touch nothing
 
   const int64_t pool_off = (int64_t)b * p.block_stride_b + (int64_t)slot * p.row_bytes + (int64_t)col * sizeof(VecT);
-  const int64_t plane_b = (int64_t)P * p.row_bytes;  // one (layer, K|V) plane of this session in the buffer
-  const int64_t buf_off0 = off_s * p.n_planes * p.row_bytes + t * p.row_bytes + (int64_t)col * sizeof(VecT);
+  const int64_t buf_off0 = sess_b + (int64_t)t * p.row_bytes + (int64_t)col * sizeof(VecT);
 
   const int32_t plane0 = blockIdx.y * PLANES;
   VecT v[PLANES];
 #pragma unroll
   for (int i = 0; i < PLANES; ++i) {
-    const int32_t pl = plane0 + i;
-    if (pl < p.n_planes) {
-      const int64_t bo = buf_off0 + pl * plane_b;
-      const char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
-      if (bo + (int64_t)sizeof(VecT) <= p.buf_bytes) v[i] = PACK ? load_vec<VecT, NT>(pool) : load_vec<VecT, NT>(p.buf + bo);
-    }
+    const int32_t pl = min(plane0 + i, p.n_planes - 1);  // a ragged last group repeats its last plane (same bytes)
+    const char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
+    v[i] = PACK ? load_vec<VecT, NT>(pool) : load_vec<VecT, NT>(p.buf + buf_off0 + pl * plane_b);
   }
 #pragma unroll
   for (int i = 0; i < PLANES; ++i) {
-    const int32_t pl = plane0 + i;
-    if (pl < p.n_planes) {
-      const int64_t bo = buf_off0 + pl * plane_b;
-      char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
-      if (bo + (int64_t)sizeof(VecT) <= p.buf_bytes) {
-        if (PACK)
-          store_vec<VecT, NT>(p.buf + bo, v[i]);
-        else
-          store_vec<VecT, NT>(pool, v[i]);
-      }
-    }
+    const int32_t pl = min(plane0 + i, p.n_planes - 1);
+    char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
+    if (PACK)
+      store_vec<VecT, NT>(p.buf + buf_off0 + pl * plane_b, v[i]);
+    else
+      store_vec<VecT, NT>(pool, v[i]);
   }
+}
+
+static int env_int(const char* name, int dflt) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : dflt;
 }
 
 template <typename VecT, bool PACK, int PLANES>
 static void launch_nt(bool nt, dim3 grid, const MigrateParams& p, hipStream_t stream) {
-  if (nt)
-    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, true>), grid, dim3(256), 0, stream, p);
-  else
-    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, false>), grid, dim3(256), 0, stream, p);
+  const bool uniform = p.row_shift >= 6 && env_int("SYMPH_MIGRATE_UNIFORM", 1) != 0;
+  if (uniform) {
+    if (nt)
+      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, true, true>), grid, dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, false, true>), grid, dim3(256), 0, stream, p);
+  } else {
+    if (nt)
+      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, true, false>), grid, dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, false, false>), grid, dim3(256), 0, stream, p);
+  }
 }
 
 template <typename VecT, bool PACK>
@@ -125,18 +146,19 @@ static int32_t launch_planes(int planes, bool nt, const MigrateParams& p, hipStr
   if (gx > 0x7FFFFFFFLL || gy > 65535) return SYMPH_EUNSUPPORTED;
   dim3 grid((unsigned)gx, (unsigned)gy);
   switch (planes) {
+    case 1: launch_nt<VecT, PACK, 1>(nt, grid, p, stream); break;
     case 2: launch_nt<VecT, PACK, 2>(nt, grid, p, stream); break;
+    case 3: launch_nt<VecT, PACK, 3>(nt, grid, p, stream); break;
     case 4: launch_nt<VecT, PACK, 4>(nt, grid, p, stream); break;
+    case 5: launch_nt<VecT, PACK, 5>(nt, grid, p, stream); break;
+    case 6: launch_nt<VecT, PACK, 6>(nt, grid, p, stream); break;
     case 8: launch_nt<VecT, PACK, 8>(nt, grid, p, stream); break;
     default: return SYMPH_EINVAL;
   }
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
 }
 
-static int env_int(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
+static int log2_or_neg(int64_t x) { return (x > 0 && (x & (x - 1)) == 0) ? __builtin_ctzll((unsigned long long)x) : -1; }
 
 int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_table, int32_t table_stride,
                           const int32_t* d_prefix_lens, const int64_t* d_offsets, int32_t n_sessions,
@@ -159,7 +181,9 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_t
   p.block_stride_b = c->block_stride * eb;
   p.row_bytes = (int32_t)row_bytes;
   p.vecs_per_row = (int32_t)(row_bytes / vec);
+  p.row_shift = log2_or_neg(p.vecs_per_row);
   p.block_size = c->block_size;
+  p.bs_shift = log2_or_neg(c->block_size);
   p.n_blocks = c->n_blocks;
   p.n_planes = 2 * c->n_layers;
   p.table = d_table;
@@ -171,10 +195,11 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_t
   p.buf = (char*)d_buf;
   p.buf_bytes = buf_bytes;
 
-  // Tuning knobs (development): planes per lane and non-temporal access.
-  int planes = env_int("SYMPH_MIGRATE_PLANES", 8);
-  if (planes != 2 && planes != 4 && planes != 8) planes = 8;
-  while (planes > 2 && planes > p.n_planes) planes >>= 1;
+  // Planes per lane: 4 measured best on MI355X (2 and 3 close, 1 and 8 far behind). Development knobs.
+  int planes = env_int("SYMPH_MIGRATE_PLANES", 4);
+  if (planes < 1 || planes > 8 || planes == 7) planes = 4;
+  while (planes > 1 && planes > p.n_planes) --planes;
+  if (planes == 7) planes = 6;
   const bool nt = env_int("SYMPH_MIGRATE_NT", 1) != 0;
 
   if (vec == 16) return pack ? launch_planes<u32x4, true>(planes, nt, p, stream) : launch_planes<u32x4, false>(planes, nt, p, stream);
@@ -203,7 +228,7 @@ __global__ __launch_bounds__(256) void device_copy_kernel(u32x4* __restrict__ ds
 }
 
 int32_t launch_device_copy(void* d_dst, const void* d_src, int64_t bytes, hipStream_t stream) {
-  constexpr int UNROLL = 8;
+  constexpr int UNROLL = 1;  // one 16-byte vector per lane and a very wide grid measured fastest on MI355X
   const int64_t n_vec = bytes / 16;
   const int64_t g = ceil_div64(n_vec, 256 * UNROLL);
   if (g > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;

@@ -317,11 +317,36 @@ __device__ __forceinline__ void store_out_row(__bf16* op, const f32x16 (&acc)[4]
     }
 }
 
-template <int G>
+// Lanes l and l^32 hold the two halves of one query's keys.  v_permlane32_swap_b32 a, b exchanges lanes 32..63 of a
+// with lanes 0..31 of b, so starting from two copies of x it leaves a = low half twice, b = high half twice.
+// Written as inline assembly: with this compiler the builtin hands back the first register for both results.
+__device__ __forceinline__ void swap_halves(float x, float& lo_twice, float& hi_twice) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  lo_twice = a;
+  hi_twice = b;
+}
+__device__ __forceinline__ float max_across_halves(float x) {
+  float lo, hi;
+  swap_halves(x, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_across_halves(float x) {
+  float lo, hi;
+  swap_halves(x, lo, hi);
+  return lo + hi;
+}
+
+constexpr int kKsElems = kBN * kKsStride;
+constexpr int kVsElems = kBN * kVsStride;
+
+// UB: block_size >= 16, so the 16 consecutive key rows a group of 16 threads stages lie in ONE block: block ids
+// are workgroup-uniform, live in scalar registers, and a row address is scalar base + per-thread constant.
+template <int G, bool UB>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   constexpr int BMT = 128 / G;  // query tokens per tile
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[kBN * kKsStride];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[kBN * kVsStride];
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2 * kKsElems];  // double-buffered K tile [64 keys][128 d]
+  __shared__ __attribute__((aligned(16))) __bf16 Vs[2 * kVsElems];  // double-buffered V tile [64 keys][128 d]
 
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
@@ -373,33 +398,47 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int kr = tid >> 4;
   const bool has_table = p.table != nullptr && p.table_stride > 0;
   const int32_t* table_row = p.table + (int64_t)s * p.table_stride;
-  const int thr_off = kvh * kD + 8 * c;   // this thread's offset inside a token row
   const int row_elems = Hkv * kD;
+  const int thr_off = kvh * kD + 8 * c;                              // offset inside a token row (elements)
+  const unsigned voff = (unsigned)(kr * row_elems + thr_off) * 2u;   // UB: byte offset from a 16-row group's base
 
-  // block ids of the tile's four key rows of this thread, loaded one tile ahead of the K,V rows themselves so that
-  // the two dependent global reads never sit on the critical path
+  // Block ids of the tile's four 16-row groups, loaded one tile ahead of the K,V rows themselves so that the two
+  // dependent global reads never sit on the critical path.  UB: uniform (scalar registers).
   int ids[4];
   auto load_ids = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int jb = (tile * kBN + 16 * i + kr) >> lb;
-      ids[i] = has_table ? table_row[min(jb, p.table_stride - 1)] : -1;
+      const int row0 = tile * kBN + 16 * i;
+      const int jb = (UB ? row0 : row0 + kr) >> lb;
+      const int b = has_table ? table_row[min(jb, p.table_stride - 1)] : -1;
+      ids[i] = UB ? __builtin_amdgcn_readfirstlane(b) : b;
     }
   };
   u32x4 kreg[4], vreg[4];
   bool row_ok[4];
+  bool all_ok = true;  // UB fast tiles: uniform "nothing to zero" flag for the staged tile
   auto fetch_fast = [&](int tile) {
+    all_ok = true;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int key = tile * kBN + 16 * i + kr;
+      const int row0 = tile * kBN + 16 * i;
       const int b = ids[i];
       row_ok[i] = (unsigned)b < (unsigned)p.n_blocks;
-      const int64_t e = (int64_t)(row_ok[i] ? b : 0) * p.block_stride + (key & bs_mask) * row_elems + thr_off;
-      kreg[i] = *reinterpret_cast<const u32x4*>(p.k_layer + e);
-      vreg[i] = *reinterpret_cast<const u32x4*>(p.v_layer + e);
+      if constexpr (UB) {
+        all_ok = all_ok && row_ok[i];
+        const int64_t sbase = ((int64_t)(row_ok[i] ? b : 0) * p.block_stride + (int64_t)(row0 & bs_mask) * row_elems) * 2;
+        kreg[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.k_layer) + sbase + voff);
+        vreg[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.v_layer) + sbase + voff);
+      } else {
+        all_ok = false;
+        const int64_t e = (int64_t)(row_ok[i] ? b : 0) * p.block_stride + ((row0 + kr) & bs_mask) * row_elems + thr_off;
+        kreg[i] = *reinterpret_cast<const u32x4*>(p.k_layer + e);
+        vreg[i] = *reinterpret_cast<const u32x4*>(p.v_layer + e);
+      }
     }
   };
   auto fetch_general = [&](int tile) {  // unconditional loads (a safe dummy address for absent rows), zeroed when staged
+    all_ok = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int key = tile * kBN + 16 * i + kr;
@@ -421,13 +460,22 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     else
       fetch_general(tile);
   };
-  auto stage = [&]() {
+  auto stage = [&](int buf) {
+    __bf16* ks = Ks + buf * kKsElems + kr * kKsStride + 8 * c;
+    __bf16* vs = Vs + buf * kVsElems + kr * kVsStride + 8 * c;
+    if (all_ok) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = 16 * i + kr;
+      for (int i = 0; i < 4; ++i) {
+        *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = kreg[i];
+        *reinterpret_cast<u32x4*>(vs + 16 * i * kVsStride) = vreg[i];
+      }
+    } else {
       const u32x4 z = u32x4{0u, 0u, 0u, 0u};
-      *reinterpret_cast<u32x4*>(&Ks[row * kKsStride + 8 * c]) = row_ok[i] ? kreg[i] : z;
-      *reinterpret_cast<u32x4*>(&Vs[row * kVsStride + 8 * c]) = row_ok[i] ? vreg[i] : z;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = row_ok[i] ? kreg[i] : z;
+        *reinterpret_cast<u32x4*>(vs + 16 * i * kVsStride) = row_ok[i] ? vreg[i] : z;
+      }
     }
   };
 
@@ -446,30 +494,45 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int i16 = lane & 15;
   const __bf16* v_rd = &Vs[(8 * g2 + (i16 >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3)];
 
+  // prologue: tile_begin staged in buffer 0, tile_begin+1 in flight
   load_ids(tile_begin);
   fetch(tile_begin);
   if (tile_begin + 1 < tile_end) load_ids(tile_begin + 1);
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    __syncthreads();
-    stage();
-    __syncthreads();
-    if (tile + 1 < tile_end) {
-      fetch(tile + 1);
-      if (tile + 2 < tile_end) load_ids(tile + 2);
-    }
+  stage(0);
+  if (tile_begin + 1 < tile_end) {
+    fetch(tile_begin + 1);
+    if (tile_begin + 2 < tile_end) load_ids(tile_begin + 2);
+  }
+  __syncthreads();
 
-    // S^T tile: 64 keys x 32 queries per wave
-    f32x16 sc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
-#pragma unroll
-      for (int st = 0; st < 8; ++st) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(k_rd + kb * 32 * kKsStride + 16 * st);
-        sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[st], sc[kb], 0, 0, 0);
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int cur = (tile - tile_begin) & 1;
+    if (tile + 1 < tile_end) {  // the other buffer was last read before the barrier that ended the previous iteration
+      stage(cur ^ 1);
+      if (tile + 2 < tile_end) {
+        fetch(tile + 2);
+        if (tile + 3 < tile_end) load_ids(tile + 3);
       }
     }
+    const __bf16* k_cur = k_rd + cur * kKsElems;
+    const __bf16* v_cur = v_rd + cur * kVsElems;
+
+    // S^T tile: 64 keys x 32 queries per wave; K fragments of the second key block are read while the first multiplies
+    f32x16 sc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
+    bf16x8 ka[8];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 16 * st);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[0], 0, 0, 0);
+      ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 32 * kKsStride + 16 * st);
+    }
+#pragma unroll
+    for (int st = 0; st < 8; ++st) sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[1], 0, 0, 0);
 
     // causal mask (only tiles that reach past the first query's limit)
     const int key0 = tile * kBN;
@@ -489,7 +552,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_across_halves(mx);
     const float m_new = fmaxf(m_run, mx);
     // a chunk that starts past a row's causal limit has seen nothing yet: keep the exponent arguments finite
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
@@ -521,17 +584,18 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          const __bf16* vp = v_rd + (kb * 32 + 16 * u) * kVsStride + 32 * dt;
+          const __bf16* vp = v_cur + (kb * 32 + 16 * u) * kVsStride + 32 * dt;
           const s16x4 lo = lds_read_tr16(vp);
           const s16x4 hi = lds_read_tr16(vp + 4 * kVsStride);
           const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kb][u], o_acc[dt],
                                                               0, 0, 0);
         }
+    __syncthreads();
   }
 
   if (it.pslot < 0) {
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = sum_across_halves(l_run);
     if (q_valid)
       store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + head) * kD, o_acc, 1.0f / l_tot, g2);
   } else {
@@ -584,7 +648,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[dt][e] = fmaf(w, part[(dt * 16 + e) * 256], acc[dt][e]);
   }
-  const float l_tot = L + __shfl_xor(L, 32);
+  const float l_tot = sum_across_halves(L);
   if (tok < N)
     store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + (kvh * G + hh)) * kD, acc, 1.0f / l_tot, g2);
 }
@@ -715,7 +779,10 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads;
   if (g_main > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
   hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
-  hipLaunchKernelGGL((attn_mfma_kernel<G>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+  if (a.block_size >= 16)
+    hipLaunchKernelGGL((attn_mfma_kernel<G, true>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL((attn_mfma_kernel<G, false>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
   hipLaunchKernelGGL((attn_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
 }
