@@ -7,7 +7,8 @@ from dataclasses import dataclass
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsymph.so")
+# SYMPH_LIBRARY_PATH: development override to load an experimental build of the same library
+_LIB_PATH = os.environ.get("SYMPH_LIBRARY_PATH") or os.path.join(_HERE, "libsymph.so")
 _lib = None
 
 SYMPH_BF16, SYMPH_FP32 = 0, 1

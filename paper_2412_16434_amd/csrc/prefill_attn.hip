@@ -16,6 +16,14 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
+
+// Development-only timing ablations (never defined in the product build): bit 0 skips the softmax arithmetic,
+// bit 1 the global loads and staging after the prologue, bit 2 the P*V product, bit 3 the Q*K product.
+#ifndef SYMPH_DEV_ABLATE
+#define SYMPH_DEV_ABLATE 0
+#endif
+
 namespace symph {
 
 // ------------------------------------------------------------------------------------------------------------
@@ -267,6 +275,8 @@ struct MfmaParams {
   const __bf16* k_layer;
   const __bf16* v_layer;
   int64_t block_stride;
+  uint32_t block_bytes;  // block_stride in bytes (the MFMA path requires it to fit 32 bits)
+  uint32_t row_bytes;    // one token row of K (or V): n_kv_heads * 128 * 2
   int32_t n_blocks, log_bs, n_kv_heads, n_q_heads;
   const __bf16* q;
   const __bf16* k_new;
@@ -340,9 +350,18 @@ __device__ __forceinline__ float sum_across_halves(float x) {
 constexpr int kKsElems = kBN * kKsStride;
 constexpr int kVsElems = kBN * kVsStride;
 
-// UB: block_size >= 16, so the 16 consecutive key rows a group of 16 threads stages lie in ONE block: block ids
-// are workgroup-uniform, live in scalar registers, and a row address is scalar base + per-thread constant.
-template <int G, bool UB>
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// One workgroup = one work item x one kv-head: 128 query rows (G heads x 128/G tokens) against the item's key tiles.
+// Requires block_size >= 16 (a power of two): the 16 consecutive key rows that a group of 16 threads stages then lie
+// in ONE block, so block ids are workgroup-uniform, live in scalar registers, and a row address is
+// scalar base + per-thread constant.  LB = log2(block_size) when it is 4 (the common 16-token block), else 0 = runtime.
+//
+// Each wave issues at most one instruction every four cycles, so the loop over key tiles is written for a low
+// instruction count: tiles that lie wholly inside the paged prefix run through a loop that is unrolled twice (one
+// copy per LDS buffer, all LDS offsets immediate, no masking, no per-row bounds logic); the few tiles around the
+// prefix / new-turn boundary and the causal diagonal take a general path.
+template <int G, int LB>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   constexpr int BMT = 128 / G;  // query tokens per tile
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2 * kKsElems];  // double-buffered K tile [64 keys][128 d]
@@ -358,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int cu_s = p.cu_new_lens[s];
   const int N = p.cu_new_lens[s + 1] - cu_s;
   const int P = p.prefix_lens[s];
-  const int lb = p.log_bs;
+  const int lb = LB ? LB : p.log_bs;
   const int bs_mask = (1 << lb) - 1;
 
   const int tid = threadIdx.x;
@@ -400,45 +419,43 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int32_t* table_row = p.table + (int64_t)s * p.table_stride;
   const int row_elems = Hkv * kD;
   const int thr_off = kvh * kD + 8 * c;                              // offset inside a token row (elements)
-  const unsigned voff = (unsigned)(kr * row_elems + thr_off) * 2u;   // UB: byte offset from a 16-row group's base
+  const unsigned voff = (unsigned)(kr * row_elems + thr_off) * 2u;   // byte offset from a 16-row group's base
+  const char* k_bytes = reinterpret_cast<const char*>(p.k_layer);
+  const char* v_bytes = reinterpret_cast<const char*>(p.v_layer);
 
-  // Block ids of the tile's four 16-row groups, loaded one tile ahead of the K,V rows themselves so that the two
-  // dependent global reads never sit on the critical path.  UB: uniform (scalar registers).
+  // Block ids of the tile's four 16-row groups (scalar registers), loaded one tile ahead of the K,V rows themselves so
+  // that the two dependent global reads never sit on the critical path.
   int ids[4];
   auto load_ids = [&](int tile) {
+    if (has_table) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row0 = tile * kBN + 16 * i;
-      const int jb = (UB ? row0 : row0 + kr) >> lb;
-      const int b = has_table ? table_row[min(jb, p.table_stride - 1)] : -1;
-      ids[i] = UB ? __builtin_amdgcn_readfirstlane(b) : b;
+      for (int i = 0; i < 4; ++i) {
+        const int jb = (tile * kBN + 16 * i) >> lb;
+        ids[i] = __builtin_amdgcn_readfirstlane(table_row[min(jb, p.table_stride - 1)]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ids[i] = -1;
     }
   };
   u32x4 kreg[4], vreg[4];
-  bool row_ok[4];
-  bool all_ok = true;  // UB fast tiles: uniform "nothing to zero" flag for the staged tile
+  unsigned okbits = 0xF;  // bit i: the rows of group i that this thread staged exist (uniform for fast tiles)
   auto fetch_fast = [&](int tile) {
-    all_ok = true;
+    unsigned ok = 0xF;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row0 = tile * kBN + 16 * i;
-      const int b = ids[i];
-      row_ok[i] = (unsigned)b < (unsigned)p.n_blocks;
-      if constexpr (UB) {
-        all_ok = all_ok && row_ok[i];
-        const int64_t sbase = ((int64_t)(row_ok[i] ? b : 0) * p.block_stride + (int64_t)(row0 & bs_mask) * row_elems) * 2;
-        kreg[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.k_layer) + sbase + voff);
-        vreg[i] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.v_layer) + sbase + voff);
-      } else {
-        all_ok = false;
-        const int64_t e = (int64_t)(row_ok[i] ? b : 0) * p.block_stride + ((row0 + kr) & bs_mask) * row_elems + thr_off;
-        kreg[i] = *reinterpret_cast<const u32x4*>(p.k_layer + e);
-        vreg[i] = *reinterpret_cast<const u32x4*>(p.v_layer + e);
-      }
+      const unsigned b = (unsigned)ids[i];
+      const unsigned bc = min(b, (unsigned)(p.n_blocks - 1));  // out-of-range ids are never dereferenced
+      if (bc != b) ok &= ~(1u << i);
+      uint64_t off = (uint64_t)bc * p.block_bytes;
+      if (LB != 4) off += (uint64_t)((tile * kBN + 16 * i) & bs_mask) * p.row_bytes;
+      kreg[i] = *reinterpret_cast<const u32x4*>(k_bytes + off + voff);
+      vreg[i] = *reinterpret_cast<const u32x4*>(v_bytes + off + voff);
     }
+    okbits = ok;
   };
   auto fetch_general = [&](int tile) {  // unconditional loads (a safe dummy address for absent rows), zeroed when staged
-    all_ok = false;
+    unsigned ok = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int key = tile * kBN + 16 * i + kr;
@@ -451,19 +468,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       const __bf16* vp = in_pool ? p.v_layer + e_pool : (in_new ? p.v_new + e_new : p.q);
       kreg[i] = *reinterpret_cast<const u32x4*>(kp);
       vreg[i] = *reinterpret_cast<const u32x4*>(vp);
-      row_ok[i] = in_pool || in_new;
+      if (in_pool || in_new) ok |= 1u << i;
     }
+    okbits = ok;
   };
-  auto fetch = [&](int tile) {
-    if (tile < fast_end)
-      fetch_fast(tile);
-    else
-      fetch_general(tile);
-  };
+  __bf16* const k_wr = Ks + kr * kKsStride + 8 * c;
+  __bf16* const v_wr = Vs + kr * kVsStride + 8 * c;
   auto stage = [&](int buf) {
-    __bf16* ks = Ks + buf * kKsElems + kr * kKsStride + 8 * c;
-    __bf16* vs = Vs + buf * kVsElems + kr * kVsStride + 8 * c;
-    if (all_ok) {
+    __bf16* ks = k_wr + buf * kKsElems;
+    __bf16* vs = v_wr + buf * kVsElems;
+    if (okbits == 0xF) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = kreg[i];
@@ -473,8 +487,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       const u32x4 z = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = row_ok[i] ? kreg[i] : z;
-        *reinterpret_cast<u32x4*>(vs + 16 * i * kVsStride) = row_ok[i] ? vreg[i] : z;
+        *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = (okbits >> i) & 1 ? kreg[i] : z;
+        *reinterpret_cast<u32x4*>(vs + 16 * i * kVsStride) = (okbits >> i) & 1 ? vreg[i] : z;
       }
     }
   };
@@ -488,13 +502,118 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   float l_run = 0.f;        // this lane's share of the running sum
   const float cs = p.scale_log2e;
   const int q_limit = P + tok;  // last key this query may see
-  const __bf16* k_rd = &Ks[key_of_row(n) * kKsStride + 8 * g2];
+  const __bf16* const k_rd = &Ks[key_of_row(n) * kKsStride + 8 * g2];
   // transposing V read: lane group (lane/16) = 2*g2 + dhalf reads rows (keys) 8*g2 + i16/4 (+4), columns
   // 16*dhalf + 4*(i16%4) .. +3 and receives, for column d = 16*dhalf + i16, four consecutive keys
   const int i16 = lane & 15;
-  const __bf16* v_rd = &Vs[(8 * g2 + (i16 >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3)];
+  const __bf16* const v_rd = &Vs[(8 * g2 + (i16 >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3)];
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  // prologue: tile_begin staged in buffer 0, tile_begin+1 in flight
+  // One key tile: S^T = K Q^T, online softmax (one query per lane), O^T += V^T P^T.  MASKED: the tile may reach past
+  // some query's causal limit, or the work item may start past it (then a row may have seen no key at all yet).
+  auto compute = [&](const __bf16* k_cur, const __bf16* v_cur, int tile, auto masked_c) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    f32x16 sc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
+    if (!(SYMPH_DEV_ABLATE & 8)) {
+      // K fragments of the second 32-key block are read while the first block multiplies
+      bf16x8 ka[8];
+#pragma unroll
+      for (int st = 0; st < 8; ++st) ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 16 * st);
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[0], 0, 0, 0);
+        ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 32 * kKsStride + 16 * st);
+      }
+#pragma unroll
+      for (int st = 0; st < 8; ++st) sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[1], 0, 0, 0);
+    }
+    if (MASKED) {
+      const int key0 = tile * kBN;
+      if (key0 + kBN - 1 > P + t0) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int key = key0 + kb * 32 + 16 * (e >> 3) + 8 * g2 + (e & 7);
+            if (key > q_limit) sc[kb][e] = -INFINITY;
+          }
+      }
+    }
+    // online softmax; two lanes, l and l^32, share a query and split its keys
+    float mx = sc[0][0];
+    if (!(SYMPH_DEV_ABLATE & 1)) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
+      mx = max_across_halves(mx);
+    }
+    const float m_new = fmaxf(m_run, mx);
+    // a row that has seen no key yet (possible only on the MASKED path) keeps its exponent arguments finite
+    const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
+    const float mb = m_use * cs;
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pv = (SYMPH_DEV_ABLATE & 1) ? sc[kb][e] : __builtin_amdgcn_exp2f(fmaf(sc[kb][e], cs, -mb));
+        pb[kb][e >> 3][e & 7] = (__bf16)pv;
+      }
+    // row sum of the ROUNDED probabilities (the values the second product uses), two per instruction
+    float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bf16x8 v = pb[kb][u];
+        ps0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[0], v[1]}, ones, ps0, false);
+        ps1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[2], v[3]}, ones, ps1, false);
+        ps0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[4], v[5]}, ones, ps0, false);
+        ps1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[6], v[7]}, ones, ps1, false);
+      }
+    l_run = fmaf(l_run, alpha, ps0 + ps1);
+    if (__any(m_new != m_run)) {  // the running max moved for some query of this wave: rescale the accumulators
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[dt][e] *= alpha;
+    }
+    m_run = m_new;
+    if (SYMPH_DEV_ABLATE & 4) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) o_acc[kb][u] += (float)pb[kb][u][0] + (float)pb[kb][u][7];
+    } else {
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const __bf16* vp = v_cur + (kb * 32 + 16 * u) * kVsStride + 32 * dt;
+            const s16x4 lo = lds_read_tr16(vp);
+            const s16x4 hi = lds_read_tr16(vp + 4 * kVsStride);
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kb][u], o_acc[dt],
+                                                                0, 0, 0);
+          }
+    }
+  };
+
+  // prologue: tile_begin staged in buffer 0, tile_begin+1 in flight, ids of tile_begin+2 loaded
+  auto fetch = [&](int tile) {
+    if (tile < fast_end)
+      fetch_fast(tile);
+    else
+      fetch_general(tile);
+  };
   load_ids(tile_begin);
   fetch(tile_begin);
   if (tile_begin + 1 < tile_end) load_ids(tile_begin + 1);
@@ -505,92 +624,36 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   }
   __syncthreads();
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
+  int tile = tile_begin;
+  // fast loop: while tiles tile .. tile+3 all lie inside the paged prefix, two iterations per trip (buffers 0 and 1).
+  // Iteration t computes tile t from one buffer, stages tile t+1 into the other, fetches tile t+2, loads ids of t+3.
+  if (!(SYMPH_DEV_ABLATE & 2)) {
+    while (tile + 3 < fast_end) {
+      stage(1);
+      fetch_fast(tile + 2);
+      load_ids(tile + 3);
+      compute(k_rd, v_rd, tile, std::false_type{});
+      __syncthreads();
+      stage(0);
+      fetch_fast(tile + 3);
+      load_ids(tile + 4);
+      compute(k_rd + kKsElems, v_rd + kVsElems, tile + 1, std::false_type{});
+      __syncthreads();
+      tile += 2;
+    }
+  }
+  // general loop: boundary and diagonal tiles (and any leftover fast tile)
+  for (; tile < tile_end; ++tile) {
     const int cur = (tile - tile_begin) & 1;
-    if (tile + 1 < tile_end) {  // the other buffer was last read before the barrier that ended the previous iteration
+    if (tile + 1 < tile_end && !(SYMPH_DEV_ABLATE & 2)) {  // the other buffer was last read before the last barrier
       stage(cur ^ 1);
       if (tile + 2 < tile_end) {
         fetch(tile + 2);
         if (tile + 3 < tile_end) load_ids(tile + 3);
       }
     }
-    const __bf16* k_cur = k_rd + cur * kKsElems;
-    const __bf16* v_cur = v_rd + cur * kVsElems;
-
-    // S^T tile: 64 keys x 32 queries per wave; K fragments of the second key block are read while the first multiplies
-    f32x16 sc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
-    bf16x8 ka[8];
-#pragma unroll
-    for (int st = 0; st < 8; ++st) ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 16 * st);
-#pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[0], 0, 0, 0);
-      ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 32 * kKsStride + 16 * st);
-    }
-#pragma unroll
-    for (int st = 0; st < 8; ++st) sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[1], 0, 0, 0);
-
-    // causal mask (only tiles that reach past the first query's limit)
-    const int key0 = tile * kBN;
-    if (key0 + kBN - 1 > P + t0) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = key0 + kb * 32 + 16 * (e >> 3) + 8 * g2 + (e & 7);
-          if (key > q_limit) sc[kb][e] = -INFINITY;
-        }
-    }
-
-    // online softmax, one query per lane (two lanes, l and l^32, share a query and split its keys)
-    float mx = sc[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
-    mx = max_across_halves(mx);
-    const float m_new = fmaxf(m_run, mx);
-    // a chunk that starts past a row's causal limit has seen nothing yet: keep the exponent arguments finite
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
-    const float mb = m_use * cs;
-    float psum = 0.f;
-    bf16x8 pb[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float pv = __builtin_amdgcn_exp2f(fmaf(sc[kb][e], cs, -mb));
-        psum += pv;
-        pb[kb][e >> 3][e & 7] = (__bf16)pv;
-      }
-    l_run = l_run * alpha + psum;
-    if (__any(m_new != m_run)) {  // the running max moved for some query of this wave: rescale the accumulators
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o_acc[dt][e] *= alpha;
-    }
-    m_run = m_new;
-
-    // O^T += V^T P^T
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const __bf16* vp = v_cur + (kb * 32 + 16 * u) * kVsStride + 32 * dt;
-          const s16x4 lo = lds_read_tr16(vp);
-          const s16x4 hi = lds_read_tr16(vp + 4 * kVsStride);
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kb][u], o_acc[dt],
-                                                              0, 0, 0);
-        }
+    const int rb = (SYMPH_DEV_ABLATE & 2) ? 0 : cur;
+    compute(k_rd + rb * kKsElems, v_rd + rb * kVsElems, tile, std::true_type{});
     __syncthreads();
   }
 
@@ -693,7 +756,7 @@ static bool mfma_path_ok(int32_t dtype, int32_t head_dim, int32_t n_q_heads, int
   if (dtype != SYMPH_BF16 || head_dim != 128) return false;
   const int G = n_q_heads / n_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return false;
-  return block_size > 0 && (block_size & (block_size - 1)) == 0;
+  return block_size >= 16 && (block_size & (block_size - 1)) == 0;
 }
 
 int64_t prefill_attn_workspace_bytes(const symph_kv_cache* c, int32_t n_sessions, int32_t n_q_heads,
@@ -756,6 +819,8 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.k_layer = (const __bf16*)a.k_layer;
   p.v_layer = (const __bf16*)a.v_layer;
   p.block_stride = a.block_stride;
+  p.block_bytes = (uint32_t)(a.block_stride * 2);
+  p.row_bytes = (uint32_t)a.n_kv_heads * kD * 2u;
   p.n_blocks = a.n_blocks;
   p.log_bs = __builtin_ctz((unsigned)a.block_size);
   p.n_kv_heads = a.n_kv_heads;
@@ -779,10 +844,10 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads;
   if (g_main > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
   hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
-  if (a.block_size >= 16)
-    hipLaunchKernelGGL((attn_mfma_kernel<G, true>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+  if (a.block_size == 16)
+    hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
   else
-    hipLaunchKernelGGL((attn_mfma_kernel<G, false>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
   hipLaunchKernelGGL((attn_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
 }
@@ -791,7 +856,8 @@ int32_t launch_prefill_attn(const AttnArgs& a, hipStream_t stream) {
   const int G = a.n_q_heads / a.n_kv_heads;
   const bool aligned16 = (((uintptr_t)a.k_layer | (uintptr_t)a.v_layer | (uintptr_t)a.q | (uintptr_t)a.k_new |
                            (uintptr_t)a.v_new | (uintptr_t)a.out | (uintptr_t)(a.block_stride * 2)) & 15) == 0;
-  if (mfma_path_ok(a.dtype, a.head_dim, a.n_q_heads, a.n_kv_heads, a.block_size)) {
+  if (mfma_path_ok(a.dtype, a.head_dim, a.n_q_heads, a.n_kv_heads, a.block_size) &&
+      a.block_stride * 2 <= 0xFFFFFFFFLL) {
     if (!aligned16) return SYMPH_EUNSUPPORTED;
     switch (G) {
       case 1: return launch_mfma<1>(a, stream);
