@@ -19,7 +19,8 @@
 #include <type_traits>
 
 // Development-only timing ablations (never defined in the product build): bit 0 skips the softmax arithmetic,
-// bit 1 the global loads and staging after the prologue, bit 2 the P*V product, bit 3 the Q*K product.
+// bit 1 the global loads and staging after the prologue, bit 2 the P*V product, bit 3 the Q*K product,
+// bit 4 the wait for the loads, bit 5 the barrier (results are then wrong; timing only), bit 6 records clocks.
 #ifndef SYMPH_DEV_ABLATE
 #define SYMPH_DEV_ABLATE 0
 #endif
@@ -148,13 +149,14 @@ struct WorkItem {   // 32 bytes
 struct MergeItem {  // 16 bytes
   int32_t s, t0, pslot0, n_chunks;
 };
-constexpr int kHdrInts = 64;
+constexpr int kHdrInts = 128;    // [0..3] counts, [64..127] a 256-byte page of zeros (source of absent key rows)
+constexpr int kZeroPageInt = 64;
 constexpr int kPartialFloats = 256 * 66;  // per workgroup: 64 accumulators + running max + running sum per thread
 
 struct SchedParams {
   const int32_t* cu_new_lens;
   const int32_t* prefix_lens;
-  int32_t n_sessions, bmt, n_kv_heads, target, c_min;
+  int32_t n_sessions, bmt, n_kv_heads, target, target_slots, c_min, coarse_ok;
   int32_t items_bound, merges_bound, pslots_bound;
   int32_t* hdr;
   WorkItem* items;
@@ -162,38 +164,95 @@ struct SchedParams {
 };
 
 constexpr int kBN = 64;  // keys per tile
-constexpr int kSchedThreads = 1024;
-constexpr int kSchedBuckets = 1024;
+constexpr int kSchedThreads = 256;
+constexpr int kSchedBuckets = 64;      // one per lane of a wave: the bucket offsets are a single wave-level scan
+constexpr int kSchedMaxSessions = 8192;  // sessions whose unit offsets fit the scheduler's LDS table
 
 __device__ __forceinline__ int unit_tiles(int P, int N, int t0, int bmt) {
   return (P + min(N, t0 + bmt) + kBN - 1) / kBN;
 }
 
+// Inclusive scan of one int per thread across the 256-thread block; returns the block total through `total`.
+__device__ __forceinline__ int block_inclusive_scan(int v, int* wave_sums, int& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  __syncthreads();
+  if (lane == 63) wave_sums[w] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int i = 0; i < w; ++i) base += wave_sums[i];
+  total = wave_sums[0] + wave_sums[1] + wave_sums[2] + wave_sums[3];
+  return incl + base;
+}
+
+// One workgroup turns the ragged batch into the ordered work list.  All three passes run over the flat list of
+// units (session, query tile), one unit per thread per step, so a batch of one long session is as parallel as a
+// batch of many short ones.
 __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const SchedParams p) {
+  __shared__ int unit_off[kSchedMaxSessions + 1];
+  __shared__ int wave_sums[4];
   __shared__ unsigned long long total_tiles_s;
   __shared__ int hist[kSchedBuckets];
   __shared__ int n_items_s, n_merge_s, n_pslot_s, chunk_s;
   const int tid = threadIdx.x;
+  const int S = p.n_sessions;
+  if (tid >= kZeroPageInt && tid < kHdrInts) p.hdr[tid] = 0;
   if (tid == 0) {
     total_tiles_s = 0ull;
     n_items_s = 0;
     n_merge_s = 0;
     n_pslot_s = 0;
   }
-  for (int b = tid; b < kSchedBuckets; b += kSchedThreads) hist[b] = 0;
+  if (tid < kSchedBuckets) hist[tid] = 0;
+  // unit offsets: exclusive prefix sum of ceil(N_s / bmt)
+  int carry = 0;
+  for (int base = 0; base < S; base += kSchedThreads) {
+    const int s = base + tid;
+    const int nq = s < S ? (p.cu_new_lens[s + 1] - p.cu_new_lens[s] + p.bmt - 1) / p.bmt : 0;
+    int total;
+    const int incl = block_inclusive_scan(nq, wave_sums, total);
+    if (s < S) unit_off[s] = carry + incl - nq;
+    carry += total;
+  }
+  const int U = carry;
+  if (tid == 0) unit_off[S] = U;
   __syncthreads();
+  // unit u -> (session, first token, prefix length, new length)
+  auto unit = [&](int u, int& s, int& t0, int& P, int& N) {
+    int lo = 0, hi = S;  // last s with unit_off[s] <= u
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (unit_off[mid] <= u)
+        lo = mid;
+      else
+        hi = mid;
+    }
+    s = lo;
+    t0 = (u - unit_off[s]) * p.bmt;
+    P = p.prefix_lens[s];
+    N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
+  };
   // pass 1: total number of (unit, key tile) pairs
   unsigned long long mine = 0;
-  for (int s = tid; s < p.n_sessions; s += kSchedThreads) {
-    const int N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
-    const int P = p.prefix_lens[s];
-    for (int t0 = 0; t0 < N; t0 += p.bmt) mine += (unsigned long long)unit_tiles(P, N, t0, p.bmt);
+  for (int u = tid; u < U; u += kSchedThreads) {
+    int s, t0, P, N;
+    unit(u, s, t0, P, N);
+    mine += (unsigned long long)unit_tiles(P, N, t0, p.bmt);
   }
   if (mine) atomicAdd(&total_tiles_s, mine);
   __syncthreads();
   if (tid == 0) {
+    // With at least two workgroup-sized units per slot, longest-first dispatch balances well without splitting
+    // anything but the longest units; with fewer, every unit is cut so that there are about two pieces per slot.
+    const long long wg_units = (long long)U * p.n_kv_heads;
+    const int target = (p.coarse_ok && wg_units >= 2ll * p.target_slots) ? p.target_slots : p.target;
     const unsigned long long tot = total_tiles_s * (unsigned long long)p.n_kv_heads;
-    long long c = (long long)((tot + p.target - 1) / (unsigned long long)p.target);
+    long long c = (long long)((tot + target - 1) / (unsigned long long)target);
     if (c < p.c_min) c = p.c_min;
     if (c > 0x3FFFFFFF) c = 0x3FFFFFFF;
     chunk_s = (int)c;
@@ -206,60 +265,51 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     return (int)(b < 0 ? 0 : (b >= kSchedBuckets ? kSchedBuckets - 1 : b));
   };
   // pass 2: histogram of chunk lengths
-  for (int s = tid; s < p.n_sessions; s += kSchedThreads) {
-    const int N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
-    const int P = p.prefix_lens[s];
-    for (int t0 = 0; t0 < N; t0 += p.bmt) {
-      const int nt = unit_tiles(P, N, t0, p.bmt);
-      const int nc = (nt + C - 1) / C;
-      const int len = (nt + nc - 1) / nc;
-      for (int ch = 0; ch < nc; ++ch) {
-        const int tb = ch * len, te = min(nt, tb + len);
-        if (te > tb) atomicAdd(&hist[bucket_of(te - tb)], 1);
-      }
-    }
+  for (int u = tid; u < U; u += kSchedThreads) {
+    int s, t0, P, N;
+    unit(u, s, t0, P, N);
+    const int nt = unit_tiles(P, N, t0, p.bmt);
+    const int nc = (nt + C - 1) / C;
+    const int len = (nt + nc - 1) / nc;
+    const int n_full = nt / len, rem = nt - n_full * len;  // n_full chunks of len tiles and one of rem tiles
+    if (n_full) atomicAdd(&hist[bucket_of(len)], n_full);
+    if (rem) atomicAdd(&hist[bucket_of(rem)], 1);
   }
   __syncthreads();
-  if (tid == 0) {  // exclusive prefix sum: hist[b] becomes the first list position of bucket b
-    int run = 0;
-    for (int b = 0; b < kSchedBuckets; ++b) {
-      const int h = hist[b];
-      hist[b] = run;
-      run += h;
+  if (tid < kSchedBuckets) {  // wave 0: exclusive prefix sum, hist[b] becomes the first list position of bucket b
+    const int h = hist[tid];
+    int incl = h;
+#pragma unroll
+    for (int o = 1; o < kSchedBuckets; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (tid >= o) incl += up;
     }
-    n_items_s = run;
+    hist[tid] = incl - h;
+    if (tid == kSchedBuckets - 1) n_items_s = incl;
   }
   __syncthreads();
   // pass 3: emit items
-  for (int s = tid; s < p.n_sessions; s += kSchedThreads) {
-    const int N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
-    const int P = p.prefix_lens[s];
-    for (int t0 = 0; t0 < N; t0 += p.bmt) {
-      const int nt = unit_tiles(P, N, t0, p.bmt);
-      const int nc = (nt + C - 1) / C;
-      const int len = (nt + nc - 1) / nc;
-      int n_real = 0;
-      for (int ch = 0; ch < nc; ++ch)
-        if (min(nt, (ch + 1) * len) > ch * len) ++n_real;
-      int pslot0 = -1;
-      if (n_real > 1) {
-        pslot0 = atomicAdd(&n_pslot_s, n_real);
-        const int mi = atomicAdd(&n_merge_s, 1);
-        if (mi < p.merges_bound && pslot0 + n_real <= p.pslots_bound) {
-          p.merges[mi] = MergeItem{s, t0, pslot0, n_real};
-        } else {
-          pslot0 = -2;  // cannot happen while the host-side bounds hold; fall back to not emitting the unit
-        }
+  for (int u = tid; u < U; u += kSchedThreads) {
+    int s, t0, P, N;
+    unit(u, s, t0, P, N);
+    const int nt = unit_tiles(P, N, t0, p.bmt);
+    const int nc = (nt + C - 1) / C;
+    const int len = (nt + nc - 1) / nc;
+    const int n_real = (nt + len - 1) / len;
+    int pslot0 = -1;
+    if (n_real > 1) {
+      pslot0 = atomicAdd(&n_pslot_s, n_real);
+      const int mi = atomicAdd(&n_merge_s, 1);
+      if (mi < p.merges_bound && pslot0 + n_real <= p.pslots_bound) {
+        p.merges[mi] = MergeItem{s, t0, pslot0, n_real};
+      } else {
+        continue;  // cannot happen while the host-side bounds hold
       }
-      if (pslot0 == -2) continue;
-      int k = 0;
-      for (int ch = 0; ch < nc; ++ch) {
-        const int tb = ch * len, te = min(nt, tb + len);
-        if (te <= tb) continue;
-        const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
-        if (pos < p.items_bound) p.items[pos] = WorkItem{s, t0, tb, te, pslot0 < 0 ? -1 : pslot0 + k, 0, 0, 0};
-        ++k;
-      }
+    }
+    for (int ch = 0; ch < n_real; ++ch) {
+      const int tb = ch * len, te = min(nt, tb + len);
+      const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
+      if (pos < p.items_bound) p.items[pos] = WorkItem{s, t0, tb, te, pslot0 < 0 ? -1 : pslot0 + ch, 0, 0, 0};
     }
   }
   __syncthreads();
@@ -293,9 +343,7 @@ struct MfmaParams {
   float* partials;
 };
 
-constexpr int kD = 128;         // head_dim
-constexpr int kKsStride = 136;  // bf16 per K row in LDS: 272 B, so 16-byte reads of 16 different rows cover all banks
-constexpr int kVsStride = 160;  // bf16 per V row in LDS: 320 B, so the 4 rows of a transposing read are 16 banks apart
+constexpr int kD = 128;  // head_dim
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -347,29 +395,47 @@ __device__ __forceinline__ float sum_across_halves(float x) {
   return lo + hi;
 }
 
-constexpr int kKsElems = kBN * kKsStride;
-constexpr int kVsElems = kBN * kVsStride;
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// LDS tile layout shared by K and V (64 key rows x 256 bytes): rows are stored in groups of four; a group is the
+// 1 KiB that one wave writes with one direct global->LDS load (lane l lands at group base + 16*l), groups are
+// kGroupBytes apart (16 bytes of padding), and inside row r of a group the 16-byte chunk c sits at position
+// c ^ ((r & 3) << 2).  With this, the 16 rows that a quarter-wave reads with ds_read_b128 (K fragments) and the
+// 4 rows x 32 bytes that 16 lanes read with ds_read_b64_tr_b16 (V fragments) each cover all banks once.
+constexpr int kGroupBytes = 1024 + 16;
+constexpr int kTileBytes = 16 * kGroupBytes;  // 16640
+
+#define SYMPH_GLDS16(src, dst)                                                                       \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),             \
+                                   (__attribute__((address_space(3))) void*)(dst), 16, 0, 0)
+
 // One workgroup = one work item x one kv-head: 128 query rows (G heads x 128/G tokens) against the item's key tiles.
-// Requires block_size >= 16 (a power of two): the 16 consecutive key rows that a group of 16 threads stages then lie
-// in ONE block, so block ids are workgroup-uniform, live in scalar registers, and a row address is
-// scalar base + per-thread constant.  LB = log2(block_size) when it is 4 (the common 16-token block), else 0 = runtime.
+// Requires block_size >= 16 (a power of two): the 16 consecutive key rows of a staging group then lie in ONE block, so
+// block ids are workgroup-uniform and a row address is scalar base + per-lane constant.
+// LB = log2(block_size) when it is 4 (the common 16-token block), else 0 = runtime.
 //
-// Each wave issues at most one instruction every four cycles, so the loop over key tiles is written for a low
-// instruction count: tiles that lie wholly inside the paged prefix run through a loop that is unrolled twice (one
-// copy per LDS buffer, all LDS offsets immediate, no masking, no per-row bounds logic); the few tiles around the
-// prefix / new-turn boundary and the causal diagonal take a general path.
+// Pipeline, iteration j (tiles are double-buffered in LDS, buffers are separate arrays so that the compiler can tell
+// which loads an LDS read has to wait for):
+//   start : direct global->LDS loads of K(j+2) and V(j+1) are issued (no registers, no LDS store instructions);
+//   block : S(j+1) = K(j+1) Q^T on the matrix cores  ||  online softmax of S(j) on the vector ALU  -> P(j);
+//   then  : O += V(j)^T P(j);   end: wait for the loads, one barrier.
+// The first product of the NEXT tile is independent of the softmax of the current one, so one wave keeps the matrix
+// pipe and the vector ALU busy at the same time instead of alternating between them.
 template <int G, int LB>
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   constexpr int BMT = 128 / G;  // query tokens per tile
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[2 * kKsElems];  // double-buffered K tile [64 keys][128 d]
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[2 * kVsElems];  // double-buffered V tile [64 keys][128 d]
+  __shared__ __attribute__((aligned(16))) char K0[kTileBytes];
+  __shared__ __attribute__((aligned(16))) char K1[kTileBytes];
+  __shared__ __attribute__((aligned(16))) char V0[kTileBytes];
+  __shared__ __attribute__((aligned(16))) char V1[kTileBytes];
 
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
   if (item_idx >= p.hdr[0]) return;
+#if SYMPH_DEV_ABLATE & 64
+  const long long dev_c0 = clock64(), dev_w0 = wall_clock64();
+#endif
   const int kvh = blockIdx.x - item_idx * Hkv;
   const WorkItem it = p.items[item_idx];
   const int s = it.s;
@@ -381,7 +447,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int bs_mask = (1 << lb) - 1;
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int n = lane & 31;  // query column of this lane inside the wave's 32 rows; also its A-operand row
   const int g2 = lane >> 5;
@@ -409,22 +475,22 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 
   const int total_keys = P + N;
   const int tile_begin = it.tile_begin, tile_end = it.tile_end;
-  // tiles below fast_end lie entirely inside the paged prefix: every row comes from the pool, nothing is masked
+  // tiles below fast_end lie entirely inside the paged prefix: every row comes from the pool
   const int fast_end = min(tile_end, P / kBN);
 
-  // staging map: thread -> 16-byte chunk c of key rows kr, kr+16, kr+32, kr+48 of the tile
-  const int c = tid & 15;
-  const int kr = tid >> 4;
+  // ---- global -> LDS: wave w writes row group 4*i + w (rows 16*i + 4*w .. +3 of the tile) with its i-th load;
+  // lane l covers row 4*w + l/16 of the 16-row group and holds logical chunk (l % 16) ^ ((l/16) << 2) of it.
   const bool has_table = p.table != nullptr && p.table_stride > 0;
   const int32_t* table_row = p.table + (int64_t)s * p.table_stride;
-  const int row_elems = Hkv * kD;
-  const int thr_off = kvh * kD + 8 * c;                              // offset inside a token row (elements)
-  const unsigned voff = (unsigned)(kr * row_elems + thr_off) * 2u;   // byte offset from a 16-row group's base
+  const int dma_row = 4 * wave + (lane >> 4);                          // row inside a 16-row group
+  const int dma_chunk = (lane & 15) ^ (((lane >> 4) & 3) << 2);        // logical 16-byte chunk this lane fetches
+  const unsigned row_bytes = p.row_bytes;
+  const unsigned voff = (unsigned)dma_row * row_bytes + (unsigned)kvh * 256u + (unsigned)dma_chunk * 16u;
   const char* k_bytes = reinterpret_cast<const char*>(p.k_layer);
   const char* v_bytes = reinterpret_cast<const char*>(p.v_layer);
+  const char* zero_page = reinterpret_cast<const char*>(p.hdr + kZeroPageInt) + (lane & 15) * 16;
 
-  // Block ids of the tile's four 16-row groups (scalar registers), loaded one tile ahead of the K,V rows themselves so
-  // that the two dependent global reads never sit on the critical path.
+  // Block ids of the tile's four 16-row groups (scalar registers), loaded one tile ahead of the rows themselves.
   int ids[4];
   auto load_ids = [&](int tile) {
     if (has_table) {
@@ -438,60 +504,56 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       for (int i = 0; i < 4; ++i) ids[i] = -1;
     }
   };
-  u32x4 kreg[4], vreg[4];
-  unsigned okbits = 0xF;  // bit i: the rows of group i that this thread staged exist (uniform for fast tiles)
-  auto fetch_fast = [&](int tile) {
-    unsigned ok = 0xF;
+  // Issue the loads of one tile of K or of V into an LDS buffer.  Rows that do not exist (past the session's keys, or
+  // named by a block id outside the cache) are read from the page of zeros, so they are finite and add nothing.
+  auto issue_tile = [&](const char* pool_bytes, const __bf16* new_rows, char* lds_buf, int tile) {
+    bool fast = tile < fast_end;
+    if (fast) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const unsigned b = (unsigned)ids[i];
-      const unsigned bc = min(b, (unsigned)(p.n_blocks - 1));  // out-of-range ids are never dereferenced
-      if (bc != b) ok &= ~(1u << i);
-      uint64_t off = (uint64_t)bc * p.block_bytes;
-      if (LB != 4) off += (uint64_t)((tile * kBN + 16 * i) & bs_mask) * p.row_bytes;
-      kreg[i] = *reinterpret_cast<const u32x4*>(k_bytes + off + voff);
-      vreg[i] = *reinterpret_cast<const u32x4*>(v_bytes + off + voff);
+      for (int i = 0; i < 4; ++i) fast = fast && (unsigned)ids[i] < (unsigned)p.n_blocks;
     }
-    okbits = ok;
-  };
-  auto fetch_general = [&](int tile) {  // unconditional loads (a safe dummy address for absent rows), zeroed when staged
-    unsigned ok = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int key = tile * kBN + 16 * i + kr;
-      const int b = ids[i];
-      const bool in_pool = key < P && (key >> lb) < p.table_stride && (unsigned)b < (unsigned)p.n_blocks;
-      const bool in_new = key >= P && key < total_keys;
-      const int64_t e_pool = (int64_t)(in_pool ? b : 0) * p.block_stride + (key & bs_mask) * row_elems + thr_off;
-      const int64_t e_new = (int64_t)(cu_s + key - P) * row_elems + thr_off;
-      const __bf16* kp = in_pool ? p.k_layer + e_pool : (in_new ? p.k_new + e_new : p.q);
-      const __bf16* vp = in_pool ? p.v_layer + e_pool : (in_new ? p.v_new + e_new : p.q);
-      kreg[i] = *reinterpret_cast<const u32x4*>(kp);
-      vreg[i] = *reinterpret_cast<const u32x4*>(vp);
-      if (in_pool || in_new) ok |= 1u << i;
-    }
-    okbits = ok;
-  };
-  __bf16* const k_wr = Ks + kr * kKsStride + 8 * c;
-  __bf16* const v_wr = Vs + kr * kVsStride + 8 * c;
-  auto stage = [&](int buf) {
-    __bf16* ks = k_wr + buf * kKsElems;
-    __bf16* vs = v_wr + buf * kVsElems;
-    if (okbits == 0xF) {
+    if (fast) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = kreg[i];
-        *reinterpret_cast<u32x4*>(vs + 16 * i * kVsStride) = vreg[i];
+        uint64_t off = (uint64_t)(unsigned)ids[i] * p.block_bytes;
+        if (LB != 4) off += (uint64_t)((tile * kBN + 16 * i) & bs_mask) * row_bytes;
+        SYMPH_GLDS16(pool_bytes + off + voff, lds_buf + (4 * i + wave) * kGroupBytes);
       }
     } else {
-      const u32x4 z = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4*>(ks + 16 * i * kKsStride) = (okbits >> i) & 1 ? kreg[i] : z;
-        *reinterpret_cast<u32x4*>(vs + 16 * i * kVsStride) = (okbits >> i) & 1 ? vreg[i] : z;
+        const int key = tile * kBN + 16 * i + dma_row;
+        const unsigned b = (unsigned)ids[i];
+        const bool in_pool = key < P && (key >> lb) < p.table_stride && b < (unsigned)p.n_blocks;
+        const bool in_new = key >= P && key < total_keys;
+        const char* src = zero_page;
+        if (in_pool)
+          src = pool_bytes + (uint64_t)b * p.block_bytes + (uint64_t)(key & bs_mask) * row_bytes +
+                (unsigned)kvh * 256u + (unsigned)dma_chunk * 16u;
+        else if (in_new)
+          src = reinterpret_cast<const char*>(new_rows) + (uint64_t)(cu_s + key - P) * row_bytes +
+                (unsigned)kvh * 256u + (unsigned)dma_chunk * 16u;
+        SYMPH_GLDS16(src, lds_buf + (4 * i + wave) * kGroupBytes);
       }
     }
   };
+
+  // ---- LDS reads.  K fragment (A operand of S^T = K Q^T): lane (n, g2) reads 16 bytes of key row
+  // key_of_row(n) (+32 for the second block), logical chunk 2*st + g2.
+  const int krow = key_of_row(n);
+  const int k_lane = (krow >> 2) * kGroupBytes + (krow & 3) * 256 + g2 * 16;
+  int k_off[4];  // byte offset for st >> 1 == q: chunk pair position q ^ (row & 3)
+#pragma unroll
+  for (int q = 0; q < 4; ++q) k_off[q] = k_lane + 64 * (q ^ (krow & 3));
+  // V fragment (A operand of O^T += V^T P^T) via the transposing read: 16 lanes read 4 rows x 32 bytes and each gets
+  // one column (4 consecutive keys of one d).  Lane group lane/16 = 2*g2 + dhalf, i16 = lane % 16:
+  // row = 8*g2 + i16/4 (+ 32*kb + 16*u + 4*half), bytes 64*dt + 32*dhalf + 8*(i16 % 4) of the row.
+  const int i16 = lane & 15;
+  const int vrow = 8 * g2 + (i16 >> 2);
+  const int v_lane = (vrow >> 2) * kGroupBytes + (vrow & 3) * 256 + 32 * ((lane >> 4) & 1) + 8 * (i16 & 3);
+  int v_off[4];  // byte offset for d tile dt: chunk quad position dt ^ (row & 3)
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) v_off[dt] = v_lane + 64 * (dt ^ (vrow & 3));
 
   f32x16 o_acc[4];
 #pragma unroll
@@ -502,48 +564,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   float l_run = 0.f;        // this lane's share of the running sum
   const float cs = p.scale_log2e;
   const int q_limit = P + tok;  // last key this query may see
-  const __bf16* const k_rd = &Ks[key_of_row(n) * kKsStride + 8 * g2];
-  // transposing V read: lane group (lane/16) = 2*g2 + dhalf reads rows (keys) 8*g2 + i16/4 (+4), columns
-  // 16*dhalf + 4*(i16%4) .. +3 and receives, for column d = 16*dhalf + i16, four consecutive keys
-  const int i16 = lane & 15;
-  const __bf16* const v_rd = &Vs[(8 * g2 + (i16 >> 2)) * kVsStride + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3)];
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  // One key tile: S^T = K Q^T, online softmax (one query per lane), O^T += V^T P^T.  MASKED: the tile may reach past
-  // some query's causal limit, or the work item may start past it (then a row may have seen no key at all yet).
-  auto compute = [&](const __bf16* k_cur, const __bf16* v_cur, int tile, auto masked_c) {
-    constexpr bool MASKED = decltype(masked_c)::value;
-    f32x16 sc[2];
+  // S^T of one tile (64 keys x 32 queries per wave) on the matrix cores
+  auto qk = [&](const char* kbuf, f32x16 (&sc)[2]) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
-    if (!(SYMPH_DEV_ABLATE & 8)) {
-      // K fragments of the second 32-key block are read while the first block multiplies
-      bf16x8 ka[8];
+      if (!(SYMPH_DEV_ABLATE & 8)) {
 #pragma unroll
-      for (int st = 0; st < 8; ++st) ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 16 * st);
-#pragma unroll
-      for (int st = 0; st < 8; ++st) {
-        sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[0], 0, 0, 0);
-        ka[st] = *reinterpret_cast<const bf16x8*>(k_cur + 32 * kKsStride + 16 * st);
-      }
-#pragma unroll
-      for (int st = 0; st < 8; ++st) sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[st], qreg[st], sc[1], 0, 0, 0);
-    }
-    if (MASKED) {
-      const int key0 = tile * kBN;
-      if (key0 + kBN - 1 > P + t0) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int key = key0 + kb * 32 + 16 * (e >> 3) + 8 * g2 + (e & 7);
-            if (key > q_limit) sc[kb][e] = -INFINITY;
-          }
+        for (int st = 0; st < 8; ++st) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbuf + k_off[st >> 1] + 32 * (st & 1) + kb * 8 * kGroupBytes);
+          sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[st], sc[kb], 0, 0, 0);
+        }
       }
     }
-    // online softmax; two lanes, l and l^32, share a query and split its keys
+  };
+  // causal mask: only tiles that reach past the first query's limit
+  auto mask = [&](f32x16 (&sc)[2], int tile) {
+    const int key0 = tile * kBN;
+    if (key0 + kBN - 1 > P + t0) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int key = key0 + kb * 32 + 16 * (e >> 3) + 8 * g2 + (e & 7);
+          if (key > q_limit) sc[kb][e] = -INFINITY;
+        }
+    }
+  };
+  // online softmax on the vector ALU, one query per lane (lanes l and l^32 split its keys), in two steps:
+  // running max and the factor by which everything accumulated so far has to be rescaled ...
+  auto softmax_max = [&](const f32x16 (&sc)[2], float& mb, float& alpha) {
     float mx = sc[0][0];
     if (!(SYMPH_DEV_ABLATE & 1)) {
 #pragma unroll
@@ -553,11 +606,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       mx = max_across_halves(mx);
     }
     const float m_new = fmaxf(m_run, mx);
-    // a row that has seen no key yet (possible only on the MASKED path) keeps its exponent arguments finite
-    const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
-    const float mb = m_use * cs;
-    bf16x8 pb[2][2];
+    // a work item that starts past a row's causal limit has seen no key of that row yet: keep the arguments finite
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float a = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
+    mb = m_use * cs;
+    l_run *= a;
+    alpha = (m_new != m_run) ? a : 1.0f;
+    m_run = m_new;
+  };
+  // ... then the bf16 probabilities and their row sum
+  auto softmax_exp = [&](const f32x16 (&sc)[2], float mb, bf16x8 (&pb)[2][2]) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -577,86 +635,129 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         ps0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[4], v[5]}, ones, ps0, false);
         ps1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[6], v[7]}, ones, ps1, false);
       }
-    l_run = fmaf(l_run, alpha, ps0 + ps1);
-    if (__any(m_new != m_run)) {  // the running max moved for some query of this wave: rescale the accumulators
+    l_run += ps0 + ps1;
+  };
+  auto rescale = [&](float alpha) {
+    if (__any(alpha != 1.0f)) {  // the running max moved for some query of this wave
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o_acc[dt][e] *= alpha;
     }
-    m_run = m_new;
+  };
+  // O^T += V^T P^T on the matrix cores
+  auto pv = [&](const char* vbuf, const bf16x8 (&pb)[2][2]) {
     if (SYMPH_DEV_ABLATE & 4) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int u = 0; u < 2; ++u) o_acc[kb][u] += (float)pb[kb][u][0] + (float)pb[kb][u][7];
-    } else {
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const __bf16* vp = v_cur + (kb * 32 + 16 * u) * kVsStride + 32 * dt;
-            const s16x4 lo = lds_read_tr16(vp);
-            const s16x4 hi = lds_read_tr16(vp + 4 * kVsStride);
-            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kb][u], o_acc[dt],
-                                                                0, 0, 0);
-          }
+      return;
     }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const char* vp = vbuf + v_off[dt] + (8 * kb + 4 * u) * kGroupBytes;
+          const s16x4 lo = lds_read_tr16(reinterpret_cast<const __bf16*>(vp));
+          const s16x4 hi = lds_read_tr16(reinterpret_cast<const __bf16*>(vp + kGroupBytes));
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kb][u], o_acc[dt],
+                                                              0, 0, 0);
+        }
+  };
+  auto wait_loads_and_sync = [&]() {
+    if (!(SYMPH_DEV_ABLATE & 16)) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's global->LDS loads have landed
+    if (!(SYMPH_DEV_ABLATE & 32)) __syncthreads();
   };
 
-  // prologue: tile_begin staged in buffer 0, tile_begin+1 in flight, ids of tile_begin+2 loaded
-  auto fetch = [&](int tile) {
-    if (tile < fast_end)
-      fetch_fast(tile);
-    else
-      fetch_general(tile);
-  };
+  // Pipeline.  Iteration j issues the loads of K(j+2) and V(j+1), then runs two INDEPENDENT pieces of work in one
+  // straight-line block so that the matrix pipe and the vector ALU are busy at the same time,
+  //     S(j+1) = K(j+1) Q^T   (matrix)      exponentials of S(j) -> P(j)   (vector),
+  // and then O += V(j)^T P(j).  A wave issues in order, so the instruction stream itself has to alternate between
+  // the two kinds; the sched_group_barrier sequence asks the scheduler for that interleaving.
+  // K(t) lives in K[t' & 1], V(t) in V[t' & 1] with t' = t - tile_begin.
+  f32x16 s_cur[2], s_nxt[2];
+  int ids_v[4];  // ids of the tile whose V rows are loaded next
   load_ids(tile_begin);
-  fetch(tile_begin);
-  if (tile_begin + 1 < tile_end) load_ids(tile_begin + 1);
-  stage(0);
+  issue_tile(k_bytes, p.k_new, K0, tile_begin);
+  issue_tile(v_bytes, p.v_new, V0, tile_begin);
   if (tile_begin + 1 < tile_end) {
-    fetch(tile_begin + 1);
-    if (tile_begin + 2 < tile_end) load_ids(tile_begin + 2);
+    load_ids(tile_begin + 1);
+    issue_tile(k_bytes, p.k_new, K1, tile_begin + 1);
   }
-  __syncthreads();
+  wait_loads_and_sync();
+  qk(K0, s_cur);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
+  if (tile_begin + 2 < tile_end) load_ids(tile_begin + 2);
 
-  int tile = tile_begin;
-  // fast loop: while tiles tile .. tile+3 all lie inside the paged prefix, two iterations per trip (buffers 0 and 1).
-  // Iteration t computes tile t from one buffer, stages tile t+1 into the other, fetches tile t+2, loads ids of t+3.
-  if (!(SYMPH_DEV_ABLATE & 2)) {
-    while (tile + 3 < fast_end) {
-      stage(1);
-      fetch_fast(tile + 2);
-      load_ids(tile + 3);
-      compute(k_rd, v_rd, tile, std::false_type{});
-      __syncthreads();
-      stage(0);
-      fetch_fast(tile + 3);
-      load_ids(tile + 4);
-      compute(k_rd + kKsElems, v_rd + kVsElems, tile + 1, std::false_type{});
-      __syncthreads();
-      tile += 2;
-    }
-  }
-  // general loop: boundary and diagonal tiles (and any leftover fast tile)
-  for (; tile < tile_end; ++tile) {
-    const int cur = (tile - tile_begin) & 1;
-    if (tile + 1 < tile_end && !(SYMPH_DEV_ABLATE & 2)) {  // the other buffer was last read before the last barrier
-      stage(cur ^ 1);
-      if (tile + 2 < tile_end) {
-        fetch(tile + 2);
-        if (tile + 3 < tile_end) load_ids(tile + 3);
+  auto iteration = [&](int j, auto par_c) {
+    constexpr int PAR = decltype(par_c)::value;
+    char* const k_same = PAR ? K1 : K0;   // held K(j), free now: receives K(j+2)
+    char* const k_other = PAR ? K0 : K1;  // holds K(j+1)
+    char* const v_same = PAR ? V1 : V0;   // holds V(j)
+    char* const v_other = PAR ? V0 : V1;  // held V(j-1), free now: receives V(j+1)
+    if (!(SYMPH_DEV_ABLATE & 2)) {
+      if (j + 1 < tile_end) {
+        int keep[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { keep[i] = ids[i]; ids[i] = ids_v[i]; }
+        issue_tile(v_bytes, p.v_new, v_other, j + 1);   // ids of tile j+1
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ids[i] = keep[i];
+      }
+      if (j + 2 < tile_end) {
+        issue_tile(k_bytes, p.k_new, k_same, j + 2);    // ids of tile j+2
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];
+        if (j + 3 < tile_end) load_ids(j + 3);
       }
     }
-    const int rb = (SYMPH_DEV_ABLATE & 2) ? 0 : cur;
-    compute(k_rd + rb * kKsElems, v_rd + rb * kVsElems, tile, std::true_type{});
-    __syncthreads();
+    mask(s_cur, j);
+    bf16x8 pb[2][2];
+    float alpha, mb;
+    softmax_max(s_cur, mb, alpha);
+    rescale(alpha);
+    qk(k_other, s_nxt);           // S(j+1)                     (garbage, and unused, when j+1 == tile_end)
+    softmax_exp(s_cur, mb, pb);   // P(j), independent of the line above
+    pv(v_same, pb);               // O += V(j)^T P(j)
+    // Requested order of the block above.  LDS reads run well ahead of the matrix instructions that consume them
+    // (an operand read issued right before its MFMA would expose the full LDS latency every time), and the
+    // exponentials are spread between the MFMAs of the first product.
+    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);      // K fragments: six reads up front
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of S(j+1)
+      if (g < 10) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);    // vector ALU: scale, convert, sum
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);    // two exponentials
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // V fragments: four operands up front
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of O
+      if (g < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) s_cur[kb] = s_nxt[kb];
+    wait_loads_and_sync();
+  };
+  for (int j = tile_begin; j < tile_end; j += 2) {
+    iteration(j, std::integral_constant<int, 0>{});
+    if (j + 1 < tile_end) iteration(j + 1, std::integral_constant<int, 1>{});
   }
 
+#if SYMPH_DEV_ABLATE & 64
+  if (blockIdx.x == 0 && tid == 0) {  // shader-clock ticks and 100 MHz ticks spent by workgroup 0
+    long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16);
+    t[0] = clock64() - dev_c0;
+    t[1] = wall_clock64() - dev_w0;
+    t[2] = tile_end - tile_begin;
+  }
+#endif
   if (it.pslot < 0) {
     const float l_tot = sum_across_halves(l_run);
     if (q_valid)
@@ -674,13 +775,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 }
 
 // Combine the chunks of a split unit: out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^((m_c - max_c m_c) * cs).
+// One workgroup per (unit, kv-head, 32-wide slice of d), same thread -> (row, d) mapping as the main kernel.
 template <int G>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
   constexpr int BMT = 128 / G;
   const int Hkv = p.n_kv_heads;
-  const int mi = blockIdx.x / Hkv;
+  const int dt = blockIdx.x & 3;
+  const int rest = blockIdx.x >> 2;
+  const int mi = rest / Hkv;
   if (mi >= p.hdr[2]) return;
-  const int kvh = blockIdx.x - mi * Hkv;
+  const int kvh = rest - mi * Hkv;
   const MergeItem m = p.merges[mi];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -695,11 +799,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
   const int64_t chunk_stride = (int64_t)Hkv * kPartialFloats;
   float M = -INFINITY;
   for (int ch = 0; ch < m.n_chunks; ++ch) M = fmaxf(M, base[ch * chunk_stride + 64 * 256]);
-  f32x16 acc[4];
+  float acc[16];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[dt][e] = 0.f;
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   float L = 0.f;
   for (int ch = 0; ch < m.n_chunks; ++ch) {
     const float* part = base + ch * chunk_stride;
@@ -707,13 +809,20 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
     const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mc - M) * cs);
     L += w * part[65 * 256];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[dt][e] = fmaf(w, part[(dt * 16 + e) * 256], acc[dt][e]);
+    for (int e = 0; e < 16; ++e) acc[e] = fmaf(w, part[(dt * 16 + e) * 256], acc[e]);
   }
   const float l_tot = sum_across_halves(L);
-  if (tok < N)
-    store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + (kvh * G + hh)) * kD, acc, 1.0f / l_tot, g2);
+  if (tok < N) {
+    const float inv = 1.0f / l_tot;
+    __bf16* op = p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + (kvh * G + hh)) * kD;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      bf16x4 v;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = (__bf16)(acc[4 * i + j] * inv);
+      *reinterpret_cast<bf16x4*>(op + 32 * dt + 4 * g2 + 8 * i) = v;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -725,7 +834,7 @@ static int env_int(const char* name, int dflt) {
 }
 
 struct MfmaPlan {
-  int32_t bmt, target, c_min, units_bound, items_bound, merges_bound, pslots_bound;
+  int32_t bmt, target, target_slots, c_min, units_bound, items_bound, merges_bound, pslots_bound;
   int64_t off_items, off_merges, off_partials, total_bytes;
 };
 
@@ -736,8 +845,9 @@ static MfmaPlan make_plan(int32_t n_sessions, int32_t n_q_heads, int32_t n_kv_he
   MfmaPlan pl;
   const int G = n_q_heads / n_kv_heads;
   pl.bmt = 128 / G;
-  pl.target = env_int("SYMPH_ATTN_TARGET", 1024);  // workgroup-sized pieces the batch is cut into (about 2 per slot)
-  if (pl.target < n_kv_heads) pl.target = n_kv_heads;
+  pl.target_slots = env_int("SYMPH_ATTN_SLOTS", 512);  // workgroups resident at once: 256 CUs x 2
+  if (pl.target_slots < n_kv_heads) pl.target_slots = n_kv_heads;
+  pl.target = 2 * pl.target_slots;                     // most pieces the batch is ever cut into (two per slot)
   pl.c_min = env_int("SYMPH_ATTN_CMIN", 8);
   if (pl.c_min < 1) pl.c_min = 1;
   pl.units_bound = total_new_tokens / pl.bmt + n_sessions;
@@ -807,6 +917,8 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   sp.bmt = pl.bmt;
   sp.n_kv_heads = a.n_kv_heads;
   sp.target = pl.target;
+  sp.target_slots = pl.target_slots;
+  sp.coarse_ok = env_int("SYMPH_ATTN_COARSE", 1);
   sp.c_min = pl.c_min;
   sp.items_bound = pl.items_bound;
   sp.merges_bound = pl.merges_bound;
@@ -841,14 +953,26 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.partials = (float*)(ws + pl.off_partials);
 
   const int64_t g_main = (int64_t)pl.items_bound * a.n_kv_heads;
-  const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads;
+  const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads * 4;
   if (g_main > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
-  hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
-  if (a.block_size == 16)
-    hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
-  else
-    hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
-  hipLaunchKernelGGL((attn_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
+  // The scheduler keeps one table entry per session in LDS: larger batches run as consecutive slices of sessions
+  // (same stream, same workspace; the bounds of the whole batch cover every slice).
+  for (int32_t s0 = 0; s0 < a.n_sessions; s0 += kSchedMaxSessions) {
+    const int32_t ns = a.n_sessions - s0 < kSchedMaxSessions ? a.n_sessions - s0 : kSchedMaxSessions;
+    sp.cu_new_lens = a.cu_new_lens + s0;
+    sp.prefix_lens = a.prefix_lens + s0;
+    sp.n_sessions = ns;
+    p.cu_new_lens = sp.cu_new_lens;
+    p.prefix_lens = sp.prefix_lens;
+    p.table = a.table ? a.table + (int64_t)s0 * a.table_stride : nullptr;
+    p.n_sessions = ns;
+    hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
+    if (a.block_size == 16)
+      hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((attn_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
+  }
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
 }
 
