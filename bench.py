@@ -24,6 +24,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the readings of the plain
+# copy kernel of known size (profiles/bench_llama8b_hbm_traffic.md); other workloads have not been measured.
+MEASURED_TRAFFIC_BYTES = {"llama8b": {"kv_migrate": 17.22e9, "attn": 3.88e8}}
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
@@ -34,6 +38,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama8b", help="workload name (default: the config the metric is quoted on)")
+    ap.add_argument("--only", choices=("all", "attn"), default="all",
+                    help="attn: time symph_prefix_prefill_attn alone on a one-layer cache (per-kernel profiles)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the CPU-baseline leg")
@@ -95,6 +101,52 @@ def cpu_baseline(cfg, sess, budget_s: float):
     }
 
 
+def attn_only(args, cfg, sess):
+    """symph_prefix_prefill_attn alone on the workload's attention batch (one-layer cache): one JSON line."""
+    import torch
+    import paper_2412_16434_amd as S
+    import workloads as W
+    dev = "cuda:0"
+    kh, vh, qh, knh, vnh = W.make_attn_inputs(cfg, sess)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    cache = S.KVCache(to_dev(kh)[None], to_dev(vh)[None])
+    q, k_new, v_new = to_dev(qh), to_dev(knh), to_dev(vnh)
+    out = torch.empty_like(q)
+    table = torch.from_numpy(sess.block_table).to(dev)
+    prefix_lens = torch.from_numpy(sess.prefix_lens).to(dev)
+    cu = torch.from_numpy(sess.cu_new_lens).to(dev)
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
+                                                     sess.max_new_len, sess.max_prefix_len)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def call():
+        S.prefix_prefill_attn(cache, 0, q, k_new, v_new, out, cu, prefix_lens, table, sess.max_new_len,
+                              sess.max_prefix_len, cfg.scale, workspace=ws if ws_bytes else None)
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms = e0.elapsed_time(e1) / args.steps
+    tflops = sess.attn_flops() / ms / 1e9
+    print(json.dumps({
+        "metric": "prefix-prefill attn TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_sessions": sess.n_sessions, "new_tokens": sess.total_new_tokens,
+                   "prefix_tokens": sess.total_prefix_tokens, "step": "prefix_prefill_attn(one layer)"},
+        "prefix_prefill_attn": {"ms": ms, "TFLOPs": tflops, "pct_mfma_bf16_peak": 100 * tflops / MFMA_BF16_PEAK_TFLOPS,
+                                "kv_GBps": sess.attn_bytes() / ms / 1e6, "flops": sess.attn_flops()},
+        "roofline": {"kernel": "attn_mfma", "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -116,6 +168,9 @@ def main():
         print("bench.py: benchmark configs are bf16", file=sys.stderr)
         sys.exit(2)
     sess = W.make_sessions(cfg)
+    if args.only == "attn":
+        attn_only(args, cfg, sess)
+        return
 
     # ---- inputs, resident in HBM before anything is timed ------------------------------------------------
     L, nb, bs = cfg.n_layers, cfg.n_blocks, cfg.block_size
@@ -239,10 +294,11 @@ def main():
         "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("kv_migrate")},
         "roofline_attn": {"kernel": "attn_mfma", "bound": "mfma", "achieved": attn_tflops,
                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                          "traffic": None},
+                          "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("attn")},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, sess, args.cpu_seconds)
