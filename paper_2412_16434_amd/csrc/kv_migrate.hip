@@ -4,9 +4,10 @@
 // The operation is a permutation copy, bound by HBM bandwidth.  Work decomposition:
 //   * the unit of indirection is one token row (n_kv_heads*head_dim elements, 2 KiB for Llama-3.1 shapes), which
 //     is contiguous both in the pool and in the buffer, so partially filled last blocks need no special path;
-//   * one lane owns one 16-byte vector of one token row and moves that vector for PLANES consecutive
-//     (layer, K|V) planes: the session lookup and the block-table read are done once and reused for every
-//     plane, and all PLANES loads are issued before the first store so each wave keeps PLANES KiB in flight;
+//   * one lane owns one 16-byte vector of one token row and moves that vector for PLANES (1 or 2) consecutive
+//     (layer, K|V) planes; the session lookup and the block-table read are wave-uniform and run on the scalar
+//     unit; loads are issued before the stores.  Little is kept in flight per lane on purpose: on MI355X one
+//     vector per lane and a very wide grid copies fastest (eight per lane loses a third of the bandwidth);
 //   * blockIdx.x walks the global token space (adjacent workgroups touch adjacent rows of the same plane),
 //     blockIdx.y walks groups of planes.
 #include "common.h"
@@ -37,17 +38,17 @@ struct MigrateParams {
   int64_t buf_bytes;
 };
 
-template <typename VecT, bool NT>
+template <typename VecT, int NT>
 __device__ __forceinline__ VecT load_vec(const char* p) {
-  if constexpr (NT)
+  if constexpr (NT & 1)
     return __builtin_nontemporal_load(reinterpret_cast<const VecT*>(p));
   else
     return *reinterpret_cast<const VecT*>(p);
 }
 
-template <typename VecT, bool NT>
+template <typename VecT, int NT>
 __device__ __forceinline__ void store_vec(char* p, VecT v) {
-  if constexpr (NT)
+  if constexpr (NT & 2)
     __builtin_nontemporal_store(v, reinterpret_cast<VecT*>(p));
   else
     *reinterpret_cast<VecT*>(p) = v;
@@ -55,7 +56,7 @@ __device__ __forceinline__ void store_vec(char* p, VecT v) {
 
 // UNIFORM: a token row is a whole number of waves (vecs_per_row is a power of two >= 64), so the token index, the
 // session search and the block-table read are wave-uniform and run once per wave on the scalar unit.
-template <typename VecT, bool PACK, int PLANES, bool NT, bool UNIFORM>
+template <typename VecT, bool PACK, int PLANES, int NT, bool UNIFORM>
 __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) {
   const int64_t gv = (int64_t)blockIdx.x * 256 + threadIdx.x;
   int64_t tg;  // token in the concatenated token space of all sessions
@@ -122,24 +123,27 @@ static int env_int(const char* name, int dflt) {
   return e ? atoi(e) : dflt;
 }
 
+template <typename VecT, bool PACK, int PLANES, int NT>
+static void launch_uniform(bool uniform, dim3 grid, const MigrateParams& p, hipStream_t stream) {
+  if (uniform)
+    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, NT, true>), grid, dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, NT, false>), grid, dim3(256), 0, stream, p);
+}
+
 template <typename VecT, bool PACK, int PLANES>
-static void launch_nt(bool nt, dim3 grid, const MigrateParams& p, hipStream_t stream) {
+static void launch_nt(int nt, dim3 grid, const MigrateParams& p, hipStream_t stream) {
   const bool uniform = p.row_shift >= 6 && env_int("SYMPH_MIGRATE_UNIFORM", 1) != 0;
-  if (uniform) {
-    if (nt)
-      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, true, true>), grid, dim3(256), 0, stream, p);
-    else
-      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, false, true>), grid, dim3(256), 0, stream, p);
-  } else {
-    if (nt)
-      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, true, false>), grid, dim3(256), 0, stream, p);
-    else
-      hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, false, false>), grid, dim3(256), 0, stream, p);
+  switch (nt & 3) {
+    case 0: launch_uniform<VecT, PACK, PLANES, 0>(uniform, grid, p, stream); break;
+    case 1: launch_uniform<VecT, PACK, PLANES, 1>(uniform, grid, p, stream); break;
+    case 2: launch_uniform<VecT, PACK, PLANES, 2>(uniform, grid, p, stream); break;
+    default: launch_uniform<VecT, PACK, PLANES, 3>(uniform, grid, p, stream); break;
   }
 }
 
 template <typename VecT, bool PACK>
-static int32_t launch_planes(int planes, bool nt, const MigrateParams& p, hipStream_t stream) {
+static int32_t launch_planes(int planes, int nt, const MigrateParams& p, hipStream_t stream) {
   const int64_t n_vec = p.total_tokens * p.vecs_per_row;
   const int64_t gx = ceil_div64(n_vec, 256);
   const int64_t gy = ceil_div64(p.n_planes, planes);
@@ -195,12 +199,14 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_t
   p.buf = (char*)d_buf;
   p.buf_bytes = buf_bytes;
 
-  // Planes per lane: 4 measured best on MI355X (2 and 3 close, 1 and 8 far behind). Development knobs.
-  int planes = env_int("SYMPH_MIGRATE_PLANES", 4);
-  if (planes < 1 || planes > 8 || planes == 7) planes = 4;
+  // Planes per lane, measured on MI355X (config 2 / config 4, TB/s read+written): gather 1 -> 6.1 / 5.6,
+  // 2 -> 5.8 / 5.9, 4 -> 5.5 / 5.7, 8 -> 3.0; scatter 1 -> 5.9 / 5.5, 2 -> 6.5 / 6.2, 4 -> 6.3 / 6.2.  One plane per
+  // lane repeats the session search for every vector, which only pays off while the search is short.
+  int planes = env_int("SYMPH_MIGRATE_PLANES", (pack && n_sessions <= 64) ? 1 : 2);
+  if (planes < 1 || planes > 8 || planes == 7) planes = 2;
   while (planes > 1 && planes > p.n_planes) --planes;
   if (planes == 7) planes = 6;
-  const bool nt = env_int("SYMPH_MIGRATE_NT", 1) != 0;
+  const int nt = env_int("SYMPH_MIGRATE_NT", 3);  // bit 0: non-temporal loads, bit 1: non-temporal stores
 
   if (vec == 16) return pack ? launch_planes<u32x4, true>(planes, nt, p, stream) : launch_planes<u32x4, false>(planes, nt, p, stream);
   return pack ? launch_planes<unsigned int, true>(planes, nt, p, stream)
