@@ -433,7 +433,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
   if (item_idx >= p.hdr[0]) return;
-#if SYMPH_DEV_ABLATE & 64
+#if SYMPH_DEV_ABLATE & (64 | 128)
   const long long dev_c0 = clock64(), dev_w0 = wall_clock64();
 #endif
   const int kvh = blockIdx.x - item_idx * Hkv;
@@ -569,16 +569,18 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // S^T of one tile (64 keys x 32 queries per wave) on the matrix cores
   auto qk = [&](const char* kbuf, f32x16 (&sc)[2]) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
-      if (!(SYMPH_DEV_ABLATE & 8)) {
+    if (!(SYMPH_DEV_ABLATE & 8)) {
+      // the two 32-key blocks alternate, so consecutive MFMAs never wait for each other's accumulator
 #pragma unroll
-        for (int st = 0; st < 8; ++st) {
+      for (int st = 0; st < 8; ++st)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
           const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbuf + k_off[st >> 1] + 32 * (st & 1) + kb * 8 * kGroupBytes);
           sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[st], sc[kb], 0, 0, 0);
         }
-      }
     }
   };
   // causal mask: only tiles that reach past the first query's limit
@@ -655,11 +657,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       return;
     }
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int dt = 0; dt < 4; ++dt) {  // the four d tiles alternate: independent accumulators back to back
           const char* vp = vbuf + v_off[dt] + (8 * kb + 4 * u) * kGroupBytes;
           const s16x4 lo = lds_read_tr16(reinterpret_cast<const __bf16*>(vp));
           const s16x4 hi = lds_read_tr16(reinterpret_cast<const __bf16*>(vp + kGroupBytes));
@@ -673,12 +675,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     if (!(SYMPH_DEV_ABLATE & 32)) __syncthreads();
   };
 
-  // Pipeline.  Iteration j issues the loads of K(j+2) and V(j+1), then runs two INDEPENDENT pieces of work in one
-  // straight-line block so that the matrix pipe and the vector ALU are busy at the same time,
-  //     S(j+1) = K(j+1) Q^T   (matrix)      exponentials of S(j) -> P(j)   (vector),
-  // and then O += V(j)^T P(j).  A wave issues in order, so the instruction stream itself has to alternate between
-  // the two kinds; the sched_group_barrier sequence asks the scheduler for that interleaving.
-  // K(t) lives in K[t' & 1], V(t) in V[t' & 1] with t' = t - tile_begin.
+  // Pipeline.  K(t) lives in K[t' & 1], V(t) in V[t' & 1] with t' = t - tile_begin.  Iteration j issues the loads
+  // of K(j+2) and V(j+1) and then runs two straight-line blocks in which the matrix pipe and the vector ALU work on
+  // INDEPENDENT data, so that one wave keeps both busy:
+  //   block A:  S(j+1) = K(j+1) Q^T   (matrix)   ||   exponentials of S(j) -> P(j), row sums     (vector)
+  //   block B:  O += V(j)^T P(j)      (matrix)   ||   running max / rescale factor of S(j+1)      (vector)
+  // A wave issues in order, so the instruction stream itself has to alternate between the two kinds; the
+  // sched_group_barrier sequences ask the scheduler for that interleaving and for LDS reads that run several matrix
+  // instructions ahead of their use (a read issued right before its MFMA exposes the full LDS latency every time).
   f32x16 s_cur[2], s_nxt[2];
   int ids_v[4];  // ids of the tile whose V rows are loaded next
   load_ids(tile_begin);
@@ -693,6 +697,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
   if (tile_begin + 2 < tile_end) load_ids(tile_begin + 2);
+  float mb_cur, alpha_cur;
+  mask(s_cur, tile_begin);
+  softmax_max(s_cur, mb_cur, alpha_cur);
 
   auto iteration = [&](int j, auto par_c) {
     constexpr int PAR = decltype(par_c)::value;
@@ -700,6 +707,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     char* const k_other = PAR ? K0 : K1;  // holds K(j+1)
     char* const v_same = PAR ? V1 : V0;   // holds V(j)
     char* const v_other = PAR ? V0 : V1;  // held V(j-1), free now: receives V(j+1)
+    rescale(alpha_cur);
     if (!(SYMPH_DEV_ABLATE & 2)) {
       if (j + 1 < tile_end) {
         int keep[4];
@@ -716,17 +724,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         if (j + 3 < tile_end) load_ids(j + 3);
       }
     }
-    mask(s_cur, j);
+    // ---- block A
     bf16x8 pb[2][2];
-    float alpha, mb;
-    softmax_max(s_cur, mb, alpha);
-    rescale(alpha);
-    qk(k_other, s_nxt);           // S(j+1)                     (garbage, and unused, when j+1 == tile_end)
-    softmax_exp(s_cur, mb, pb);   // P(j), independent of the line above
-    pv(v_same, pb);               // O += V(j)^T P(j)
-    // Requested order of the block above.  LDS reads run well ahead of the matrix instructions that consume them
-    // (an operand read issued right before its MFMA would expose the full LDS latency every time), and the
-    // exponentials are spread between the MFMAs of the first product.
+    qk(k_other, s_nxt);                 // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
+    softmax_exp(s_cur, mb_cur, pb);     // P(j)
     __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);      // K fragments: six reads up front
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
@@ -735,14 +736,35 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);    // vector ALU: scale, convert, sum
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);    // two exponentials
     }
+    // keep the probabilities (and with them the exponentials) in this block: without a use here the compiler sinks
+    // them past the branch below, next to the second product
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[kb][u]));
+    asm volatile("" : "+v"(l_run));
+    mask(s_nxt, j + 1);
+    // ---- block B
+    const float m_keep = m_run, l_keep = l_run;
+    float mb_nxt, alpha_nxt;
+    pv(v_same, pb);                              // O += V(j)^T P(j)
+    softmax_max(s_nxt, mb_nxt, alpha_nxt);       // statistics of S(j+1)
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // V fragments: four operands up front
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of O
       if (g < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);    // running-max chain
+    }
+    if (j + 1 >= tile_end) {  // there was no tile j+1: undo the statistics computed from garbage
+      m_run = m_keep;
+      l_run = l_keep;
+      alpha_nxt = 1.0f;
     }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) s_cur[kb] = s_nxt[kb];
+    mb_cur = mb_nxt;
+    alpha_cur = alpha_nxt;
     wait_loads_and_sync();
   };
   for (int j = tile_begin; j < tile_end; j += 2) {
@@ -750,6 +772,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     if (j + 1 < tile_end) iteration(j + 1, std::integral_constant<int, 1>{});
   }
 
+#if SYMPH_DEV_ABLATE & 128
+  if (tid == 0) {  // per-workgroup timeline: start, end (100 MHz ticks), tiles, XCC/CU id; into the tail of the partials
+    long long* t = reinterpret_cast<long long*>(p.partials) + (1 << 23) + 4 * (long long)blockIdx.x;
+    unsigned hwid; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+    unsigned xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    t[0] = dev_w0; t[1] = wall_clock64(); t[2] = tile_end - tile_begin; t[3] = ((long long)xcc << 32) | hwid;
+  }
+#endif
 #if SYMPH_DEV_ABLATE & 64
   if (blockIdx.x == 0 && tid == 0) {  // shader-clock ticks and 100 MHz ticks spent by workgroup 0
     long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16);
