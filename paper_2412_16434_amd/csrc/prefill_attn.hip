@@ -488,21 +488,23 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const unsigned voff = (unsigned)dma_row * row_bytes + (unsigned)kvh * 256u + (unsigned)dma_chunk * 16u;
   const char* k_bytes = reinterpret_cast<const char*>(p.k_layer);
   const char* v_bytes = reinterpret_cast<const char*>(p.v_layer);
-  const char* zero_page = reinterpret_cast<const char*>(p.hdr + kZeroPageInt) + (lane & 15) * 16;
 
-  // Block ids of the tile's four 16-row groups (scalar registers), loaded one tile ahead of the rows themselves.
-  int ids[4];
+  // Block ids of the tile's four 16-row groups.  The table entries are fetched (vector loads, every lane the same
+  // address) a whole iteration before they are needed and only then moved to scalar registers: asking for the value
+  // right after issuing the load would also wait for the K,V loads issued just before it.
+  int ids[4];   // scalar: ids of the tile whose K rows are loaded next
+  int ids_raw;  // in flight: lane i < 4 holds the id of group i of the tile after that
+  auto fetch_ids = [&](int tile) {
+    const int jb = (tile * kBN + 16 * (lane & 3)) >> lb;
+    ids_raw = has_table ? table_row[min(jb, p.table_stride - 1)] : -1;
+  };
+  auto take_ids = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ids[i] = __builtin_amdgcn_readlane(ids_raw, i);
+  };
   auto load_ids = [&](int tile) {
-    if (has_table) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int jb = (tile * kBN + 16 * i) >> lb;
-        ids[i] = __builtin_amdgcn_readfirstlane(table_row[min(jb, p.table_stride - 1)]);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) ids[i] = -1;
-    }
+    fetch_ids(tile);
+    take_ids();
   };
   // Issue the loads of one tile of K or of V into an LDS buffer.  Rows that do not exist (past the session's keys, or
   // named by a block id outside the cache) are read from the page of zeros, so they are finite and add nothing.
@@ -514,25 +516,30 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     }
     if (fast) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < ((SYMPH_DEV_ABLATE & 512) ? 2 : 4); ++i) {
         uint64_t off = (uint64_t)(unsigned)ids[i] * p.block_bytes;
         if (LB != 4) off += (uint64_t)((tile * kBN + 16 * i) & bs_mask) * row_bytes;
         SYMPH_GLDS16(pool_bytes + off + voff, lds_buf + (4 * i + wave) * kGroupBytes);
       }
     } else {
+      // rare path: its per-lane address pieces are derived here, from a lane id the optimiser cannot see through, so
+      // that they do not occupy registers throughout the main loop
+      int l = lane;
+      asm volatile("" : "+v"(l));
+      const int row = 4 * wave + (l >> 4);
+      const unsigned in_row = (unsigned)kvh * 256u + (unsigned)((l & 15) ^ (((l >> 4) & 3) << 2)) * 16u;
+      const char* const zeros = reinterpret_cast<const char*>(p.hdr + kZeroPageInt) + (l & 15) * 16;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int key = tile * kBN + 16 * i + dma_row;
+        const int key = tile * kBN + 16 * i + row;
         const unsigned b = (unsigned)ids[i];
         const bool in_pool = key < P && (key >> lb) < p.table_stride && b < (unsigned)p.n_blocks;
         const bool in_new = key >= P && key < total_keys;
-        const char* src = zero_page;
+        const char* src = zeros;
         if (in_pool)
-          src = pool_bytes + (uint64_t)b * p.block_bytes + (uint64_t)(key & bs_mask) * row_bytes +
-                (unsigned)kvh * 256u + (unsigned)dma_chunk * 16u;
+          src = pool_bytes + (uint64_t)b * p.block_bytes + (uint64_t)(key & bs_mask) * row_bytes + in_row;
         else if (in_new)
-          src = reinterpret_cast<const char*>(new_rows) + (uint64_t)(cu_s + key - P) * row_bytes +
-                (unsigned)kvh * 256u + (unsigned)dma_chunk * 16u;
+          src = reinterpret_cast<const char*>(new_rows) + (uint64_t)(cu_s + key - P) * row_bytes + in_row;
         SYMPH_GLDS16(src, lds_buf + (4 * i + wave) * kGroupBytes);
       }
     }
@@ -683,7 +690,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // A wave issues in order, so the instruction stream itself has to alternate between the two kinds; the
   // sched_group_barrier sequences ask the scheduler for that interleaving and for LDS reads that run several matrix
   // instructions ahead of their use (a read issued right before its MFMA exposes the full LDS latency every time).
-  f32x16 s_cur[2], s_nxt[2];
+#if SYMPH_DEV_ABLATE & 256
+  long long dev_ph[4] = {0, 0, 0, 0};
+  const long long dev_c0 = clock64();
+#endif
+  f32x16 s_even[2], s_odd[2];  // scores of the even and of the odd tiles (counted from tile_begin)
   int ids_v[4];  // ids of the tile whose V rows are loaded next
   load_ids(tile_begin);
   issue_tile(k_bytes, p.k_new, K0, tile_begin);
@@ -693,20 +704,25 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     issue_tile(k_bytes, p.k_new, K1, tile_begin + 1);
   }
   wait_loads_and_sync();
-  qk(K0, s_cur);
+  qk(K0, s_even);
 #pragma unroll
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
-  if (tile_begin + 2 < tile_end) load_ids(tile_begin + 2);
+  fetch_ids(tile_begin + 2);                      // taken at the top of the first iteration
   float mb_cur, alpha_cur;
-  mask(s_cur, tile_begin);
-  softmax_max(s_cur, mb_cur, alpha_cur);
+  mask(s_even, tile_begin);
+  softmax_max(s_even, mb_cur, alpha_cur);
 
-  auto iteration = [&](int j, auto par_c) {
+  auto iteration = [&](const int j, auto par_c) {
     constexpr int PAR = decltype(par_c)::value;
     char* const k_same = PAR ? K1 : K0;   // held K(j), free now: receives K(j+2)
     char* const k_other = PAR ? K0 : K1;  // holds K(j+1)
     char* const v_same = PAR ? V1 : V0;   // holds V(j)
     char* const v_other = PAR ? V0 : V1;  // held V(j-1), free now: receives V(j+1)
+    f32x16 (&s_cur)[2] = PAR ? s_odd : s_even;   // S(j)
+    f32x16 (&s_nxt)[2] = PAR ? s_even : s_odd;   // receives S(j+1)
+#if SYMPH_DEV_ABLATE & 256
+    const long long ph0 = clock64();
+#endif
     rescale(alpha_cur);
     if (!(SYMPH_DEV_ABLATE & 2)) {
       if (j + 1 < tile_end) {
@@ -717,13 +733,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) ids[i] = keep[i];
       }
-      if (j + 2 < tile_end) {
-        issue_tile(k_bytes, p.k_new, k_same, j + 2);    // ids of tile j+2
-#pragma unroll
-        for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];
-        if (j + 3 < tile_end) load_ids(j + 3);
-      }
+      if (j + 2 < tile_end) issue_tile(k_bytes, p.k_new, k_same, j + 2);
     }
+#if SYMPH_DEV_ABLATE & 256
+    const long long ph1 = clock64();
+#endif
     // ---- block A
     bf16x8 pb[2][2];
     qk(k_other, s_nxt);                 // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
@@ -743,6 +757,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[kb][u]));
     asm volatile("" : "+v"(l_run));
+#if SYMPH_DEV_ABLATE & 256
+    asm volatile("s_nop 0" ::: "memory");
+    const long long ph2 = clock64();
+#endif
     mask(s_nxt, j + 1);
     // ---- block B
     const float m_keep = m_run, l_keep = l_run;
@@ -761,17 +779,38 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       l_run = l_keep;
       alpha_nxt = 1.0f;
     }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) s_cur[kb] = s_nxt[kb];
     mb_cur = mb_nxt;
     alpha_cur = alpha_nxt;
+#if SYMPH_DEV_ABLATE & 256
+    asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
+    const long long ph3 = clock64();
+#endif
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];      // the next V tile is j+2
     wait_loads_and_sync();
+#if SYMPH_DEV_ABLATE & 256
+    const long long ph4 = clock64();
+    dev_ph[0] += ph1 - ph0; dev_ph[1] += ph2 - ph1; dev_ph[2] += ph3 - ph2; dev_ph[3] += ph4 - ph3;
+#endif
+  };
+  // Before each iteration the ids fetched an iteration ago become scalar and the fetch of the next ones starts (it
+  // completes under the wait at the end of the iteration).
+  auto step = [&](int j, auto par_c) {
+    take_ids();         // ids of tile j+2
+    fetch_ids(j + 3);   // index clamped to the table: harmless past the last tile
+    iteration(j, par_c);
   };
   for (int j = tile_begin; j < tile_end; j += 2) {
-    iteration(j, std::integral_constant<int, 0>{});
-    if (j + 1 < tile_end) iteration(j + 1, std::integral_constant<int, 1>{});
+    step(j, std::integral_constant<int, 0>{});
+    if (j + 1 < tile_end) step(j + 1, std::integral_constant<int, 1>{});
   }
 
+#if SYMPH_DEV_ABLATE & 256
+  if (blockIdx.x == 0 && (tid & 63) == 0) {  // per-phase shader clocks of each wave of workgroup 0
+    long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16) + 8 * (tid >> 6);
+    t[0] = dev_ph[0]; t[1] = dev_ph[1]; t[2] = dev_ph[2]; t[3] = dev_ph[3]; t[4] = clock64() - dev_c0; t[5] = tile_end - tile_begin;
+  }
+#endif
 #if SYMPH_DEV_ABLATE & 128
   if (tid == 0) {  // per-workgroup timeline: start, end (100 MHz ticks), tiles, XCC/CU id; into the tail of the partials
     long long* t = reinterpret_cast<long long*>(p.partials) + (1 << 23) + 4 * (long long)blockIdx.x;
