@@ -380,7 +380,7 @@ __device__ __forceinline__ void store_out_row(__bf16* op, const f32x16 (&acc)[4]
 // Written as inline assembly: with this compiler the builtin hands back the first register for both results.
 __device__ __forceinline__ void swap_halves(float x, float& lo_twice, float& hi_twice) {
   float a = x, b = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));  // a pure function of a, b: free to be scheduled
   lo_twice = a;
   hi_twice = b;
 }
@@ -509,14 +509,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // Issue the loads of one tile of K or of V into an LDS buffer.  Rows that do not exist (past the session's keys, or
   // named by a block id outside the cache) are read from the page of zeros, so they are finite and add nothing.
   auto issue_tile = [&](const char* pool_bytes, const __bf16* new_rows, char* lds_buf, int tile) {
-    bool fast = tile < fast_end;
+    // one comparison of the largest id (as unsigned: a negative id is huge)
+    const unsigned id_max = max(max((unsigned)ids[0], (unsigned)ids[1]), max((unsigned)ids[2], (unsigned)ids[3]));
+    const bool fast = tile < fast_end && id_max < (unsigned)p.n_blocks;
     if (fast) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fast = fast && (unsigned)ids[i] < (unsigned)p.n_blocks;
-    }
-    if (fast) {
-#pragma unroll
-      for (int i = 0; i < ((SYMPH_DEV_ABLATE & 512) ? 2 : 4); ++i) {
+      for (int i = 0; i < 4; ++i) {
         uint64_t off = (uint64_t)(unsigned)ids[i] * p.block_bytes;
         if (LB != 4) off += (uint64_t)((tile * kBN + 16 * i) & bs_mask) * row_bytes;
         SYMPH_GLDS16(pool_bytes + off + voff, lds_buf + (4 * i + wave) * kGroupBytes);
@@ -623,16 +621,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     alpha = (m_new != m_run) ? a : 1.0f;
     m_run = m_new;
   };
-  // ... then the bf16 probabilities and their row sum
-  auto softmax_exp = [&](const f32x16 (&sc)[2], float mb, bf16x8 (&pb)[2][2]) {
+  // ... then the bf16 probabilities, one 32-key half at a time: the first half follows the statistics directly (in
+  // the block that is otherwise almost pure matrix work), the second half runs beside the next tile's first product,
+  // so that both blocks of the pipeline carry a similar mix of matrix and vector work whatever block the other
+  // workgroup of the CU happens to be in
+  auto softmax_exp_half = [&](const f32x16& sc, float mb, bf16x8 (&pb)[2]) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float pv = (SYMPH_DEV_ABLATE & 1) ? sc[kb][e] : __builtin_amdgcn_exp2f(fmaf(sc[kb][e], cs, -mb));
-        pb[kb][e >> 3][e & 7] = (__bf16)pv;
-      }
-    // row sum of the ROUNDED probabilities (the values the second product uses), two per instruction
+    for (int e = 0; e < 16; ++e) {
+      const float pv = (SYMPH_DEV_ABLATE & 1) ? sc[e] : __builtin_amdgcn_exp2f(fmaf(sc[e], cs, -mb));
+      pb[e >> 3][e & 7] = (__bf16)pv;
+    }
+  };
+  // row sum of the ROUNDED probabilities (the values the second product uses), two per instruction
+  auto row_sum = [&](const bf16x8 (&pb)[2][2]) {
     float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -709,8 +710,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
   fetch_ids(tile_begin + 2);                      // taken at the top of the first iteration
   float mb_cur, alpha_cur;
+  bf16x8 pb[2][2];  // P(j); its first half is produced one block ahead of the second
   mask(s_even, tile_begin);
   softmax_max(s_even, mb_cur, alpha_cur);
+  softmax_exp_half(s_even[0], mb_cur, pb[0]);
 
   auto iteration = [&](const int j, auto par_c) {
     constexpr int PAR = decltype(par_c)::value;
@@ -739,16 +742,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     const long long ph1 = clock64();
 #endif
     // ---- block A
-    bf16x8 pb[2][2];
-    qk(k_other, s_nxt);                 // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
-    softmax_exp(s_cur, mb_cur, pb);     // P(j)
+    qk(k_other, s_nxt);                          // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
+    softmax_exp_half(s_cur[1], mb_cur, pb[1]);   // second half of P(j)
+    row_sum(pb);
     __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);      // K fragments: six reads up front
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of S(j+1)
       if (g < 10) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);    // vector ALU: scale, convert, sum
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);    // two exponentials
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);    // vector ALU: scale, convert, sum
+      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // one exponential
     }
     // keep the probabilities (and with them the exponentials) in this block: without a use here the compiler sinks
     // them past the branch below, next to the second product
@@ -767,13 +770,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     float mb_nxt, alpha_nxt;
     pv(v_same, pb);                              // O += V(j)^T P(j)
     softmax_max(s_nxt, mb_nxt, alpha_nxt);       // statistics of S(j+1)
+    bf16x8 pb_first[2];
+    softmax_exp_half(s_nxt[0], mb_nxt, pb_first);   // first half of P(j+1)
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // V fragments: four operands up front
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of O
       if (g < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);    // running-max chain
+      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);    // the running-max chain first, then scale and convert
+      if (g >= 8) __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
     }
+    pb[0][0] = pb_first[0];   // (garbage, and never used, when there was no tile j+1)
+    pb[0][1] = pb_first[1];
+    asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]));   // computed here, not after the barrier
     if (j + 1 >= tile_end) {  // there was no tile j+1: undo the statistics computed from garbage
       m_run = m_keep;
       l_run = l_keep;
