@@ -344,6 +344,8 @@ struct MfmaParams {
 };
 
 constexpr int kD = 128;  // head_dim
+// A row sum above this (one probability of 2^40 or more, or an overflow) makes the softmax reference stale.
+constexpr float kRefreshSum = 1.0995116e12f;  // 2^40
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -601,9 +603,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         }
     }
   };
-  // online softmax on the vector ALU, one query per lane (lanes l and l^32 split its keys), in two steps:
-  // running max and the factor by which everything accumulated so far has to be rescaled ...
-  auto softmax_max = [&](const f32x16 (&sc)[2], float& mb, float& alpha) {
+  // Online softmax on the vector ALU, one query per lane (lanes l and l^32 split its keys), with a STALE reference:
+  // probabilities are 2^((s - m_ref) * scale') for a reference m_ref that is NOT the running maximum but the maximum
+  // at the time it was last refreshed.  Numerator and denominator carry the same factor, so the result is the exact
+  // softmax as long as nothing overflows, and bf16 / fp32 keep their relative precision at any magnitude.  The
+  // reference is refreshed (below) only when a tile's row sum shows that some score exceeds it by more than
+  // kRefreshLog2, which after the first tile practically never happens; the per-tile maximum, the rescale factor
+  // and the rescaling of the accumulators thereby leave the loop.
+  // reference := max(reference, maximum of this tile), in log2 units; returns the factor by which everything
+  // accumulated so far has to be rescaled (0 for a first reference, 1 where nothing moved)
+  auto raise_reference = [&](const f32x16 (&sc)[2], float& mb) {
     float mx = sc[0][0];
     if (!(SYMPH_DEV_ABLATE & 1)) {
 #pragma unroll
@@ -612,14 +621,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
       mx = max_across_halves(mx);
     }
-    const float m_new = fmaxf(m_run, mx);
-    // a work item that starts past a row's causal limit has seen no key of that row yet: keep the arguments finite
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float a = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
-    mb = m_use * cs;
-    l_run *= a;
-    alpha = (m_new != m_run) ? a : 1.0f;
+    const float m_new = fmaxf(m_run, mx * cs);
+    // a row that has seen no key yet (a work item may start past its causal limit) keeps m_run = -inf, which the
+    // merge step reads as "no contribution"; its exponent arguments use 0 so that they stay finite
+    const float a = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
+    mb = (m_new == -INFINITY) ? 0.f : m_new;
+    return a;
   };
   // ... then the bf16 probabilities, one 32-key half at a time: the first half follows the statistics directly (in
   // the block that is otherwise almost pure matrix work), the second half runs beside the next tile's first product,
@@ -645,15 +653,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         ps0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[4], v[5]}, ones, ps0, false);
         ps1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[6], v[7]}, ones, ps1, false);
       }
-    l_run += ps0 + ps1;
+    return ps0 + ps1;
   };
-  auto rescale = [&](float alpha) {
-    if (__any(alpha != 1.0f)) {  // the running max moved for some query of this wave
+  // Refresh of a stale reference (rare): rescale what has been accumulated, redo this tile's probabilities.
+  auto refresh_reference = [&](const f32x16 (&sc)[2], float& mb, bf16x8 (&pb)[2][2], float& ps) {
+    const float a = raise_reference(sc, mb);
+    l_run *= a;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o_acc[dt][e] *= alpha;
-    }
+      for (int e = 0; e < 16; ++e) o_acc[dt][e] *= a;
+    softmax_exp_half(sc[0], mb, pb[0]);
+    softmax_exp_half(sc[1], mb, pb[1]);
+    ps = row_sum(pb);
   };
   // O^T += V^T P^T on the matrix cores
   auto pv = [&](const char* vbuf, const bf16x8 (&pb)[2][2]) {
@@ -709,10 +721,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
   fetch_ids(tile_begin + 2);                      // taken at the top of the first iteration
-  float mb_cur, alpha_cur;
+  float mb_cur;     // reference of the exponentials, in log2 units
   bf16x8 pb[2][2];  // P(j); its first half is produced one block ahead of the second
   mask(s_even, tile_begin);
-  softmax_max(s_even, mb_cur, alpha_cur);
+  raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile
   softmax_exp_half(s_even[0], mb_cur, pb[0]);
 
   auto iteration = [&](const int j, auto par_c) {
@@ -726,7 +738,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #if SYMPH_DEV_ABLATE & 256
     const long long ph0 = clock64();
 #endif
-    rescale(alpha_cur);
     if (!(SYMPH_DEV_ABLATE & 2)) {
       if (j + 1 < tile_end) {
         int keep[4];
@@ -744,7 +755,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     // ---- block A
     qk(k_other, s_nxt);                          // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
     softmax_exp_half(s_cur[1], mb_cur, pb[1]);   // second half of P(j)
-    row_sum(pb);
+    float ps = row_sum(pb);
     __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);      // K fragments: six reads up front
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
@@ -759,37 +770,52 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[kb][u]));
-    asm volatile("" : "+v"(l_run));
+    asm volatile("" : "+v"(ps));
 #if SYMPH_DEV_ABLATE & 256
     asm volatile("s_nop 0" ::: "memory");
     const long long ph2 = clock64();
 #endif
+    // The reference is stale when some score exceeds it by more than 40 in log2 units (then the row sum is huge,
+    // infinite or NaN), or when a row that had seen no key now has one.  Rare: redo this tile's probabilities from
+    // its scores, which are still in registers, against a refreshed reference.
+    if (__any(!(ps <= kRefreshSum) || (m_run == -INFINITY && ps > 0.f))) refresh_reference(s_cur, mb_cur, pb, ps);
+    l_run += ps;
     mask(s_nxt, j + 1);
     // ---- block B
-    const float m_keep = m_run, l_keep = l_run;
-    float mb_nxt, alpha_nxt;
-    pv(v_same, pb);                              // O += V(j)^T P(j)
-    softmax_max(s_nxt, mb_nxt, alpha_nxt);       // statistics of S(j+1)
+    // O += V(j)^T P(j)  ||  first half of P(j+1), in an explicit order: each of the 16 slots holds the two LDS reads
+    // of the MFMA four slots ahead, one MFMA, and the scale / exponential (/ convert) of one score; nothing moves
+    // between slots.
     bf16x8 pb_first[2];
-    softmax_exp_half(s_nxt[0], mb_nxt, pb_first);   // first half of P(j+1)
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);      // V fragments: four operands up front
+    {
+      auto v_frag = [&](int g) {  // operand of MFMA g = ((kb * 2 + u) * 4 + dt)
+        const char* vp = v_same + v_off[g & 3] + (8 * (g >> 3) + 4 * ((g >> 2) & 1)) * kGroupBytes;
+        const s16x4 lo = lds_read_tr16(reinterpret_cast<const __bf16*>(vp));
+        const s16x4 hi = lds_read_tr16(reinterpret_cast<const __bf16*>(vp + kGroupBytes));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      };
+      bf16x8 frag[16];
+      float pe[16];
 #pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of O
-      if (g < 12) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);    // the running-max chain first, then scale and convert
-      if (g >= 8) __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+      for (int g = 0; g < 4; ++g) frag[g] = v_frag(g);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < 16; ++g) {
+        if (g + 4 < 16) frag[g + 4] = v_frag(g + 4);
+        if (!(SYMPH_DEV_ABLATE & 4))
+          o_acc[g & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[g], pb[g >> 3][(g >> 2) & 1], o_acc[g & 3], 0, 0, 0);
+        pe[g] = __builtin_amdgcn_exp2f(fmaf(s_nxt[0][g], cs, -mb_cur));
+        asm volatile("" : "+v"(pe[g]));  // evaluated in this slot (a value without side effects is otherwise placed
+                                         // next to its use, after the last slot)
+        if (g & 1) {
+          pb_first[g >> 3][(g & 7) - 1] = (__bf16)pe[g - 1];
+          pb_first[g >> 3][g & 7] = (__bf16)pe[g];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     pb[0][0] = pb_first[0];   // (garbage, and never used, when there was no tile j+1)
     pb[0][1] = pb_first[1];
     asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]));   // computed here, not after the barrier
-    if (j + 1 >= tile_end) {  // there was no tile j+1: undo the statistics computed from garbage
-      m_run = m_keep;
-      l_run = l_keep;
-      alpha_nxt = 1.0f;
-    }
-    mb_cur = mb_nxt;
-    alpha_cur = alpha_nxt;
 #if SYMPH_DEV_ABLATE & 256
     asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
     const long long ph3 = clock64();
@@ -852,7 +878,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   }
 }
 
-// Combine the chunks of a split unit: out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^((m_c - max_c m_c) * cs).
+// Combine the chunks of a split unit: out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being the
+// chunk's softmax reference in log2 units (-inf: the chunk saw no key of the row).
 // One workgroup per (unit, kv-head, 32-wide slice of d), same thread -> (row, d) mapping as the main kernel.
 template <int G>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
@@ -872,7 +899,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
   const int tok = m.t0 + (r - hh * BMT);
   const int cu_s = p.cu_new_lens[m.s];
   const int N = p.cu_new_lens[m.s + 1] - cu_s;
-  const float cs = p.scale_log2e;
   const float* base = p.partials + ((int64_t)m.pslot0 * Hkv + kvh) * kPartialFloats + tid;
   const int64_t chunk_stride = (int64_t)Hkv * kPartialFloats;
   float M = -INFINITY;
@@ -884,7 +910,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
   for (int ch = 0; ch < m.n_chunks; ++ch) {
     const float* part = base + ch * chunk_stride;
     const float mc = part[64 * 256];
-    const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mc - M) * cs);
+    const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);  // references are in log2 units
     L += w * part[65 * 256];
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = fmaf(w, part[(dt * 16 + e) * 256], acc[e]);

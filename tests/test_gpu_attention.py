@@ -114,6 +114,42 @@ def test_peaked_attention_with_position_coded_values(oracle_mod, dtype):
     check(oracle_mod, cfg, sess, (k_pool, v_pool, q, k_new, v_new), label="peaked")
 
 
+@pytest.mark.parametrize("shape", ["rising", "falling", "spike", "late_giant"])
+def test_score_ranges_that_move_the_softmax_reference(oracle_mod, shape):
+    """Scores whose level changes by tens to hundreds of powers of two between key tiles: every key is a multiple
+    of one direction u and every query is u, so score(key j) = |u|^2 * amp(j).  A kernel that keeps a softmax
+    reference from an earlier tile has to notice and move it (rising, spike, late_giant) and must not lose rows
+    whose later scores lie far below it (falling)."""
+    cfg = _cfg(n_sessions=2, n_q_heads=8, n_kv_heads=2, prefix_dist=("uniform", 300, 700), new_dist=("uniform", 40, 90),
+               scale=1.0)
+    sess = W.make_sessions(cfg, 11)
+    k_pool, v_pool, q, k_new, v_new = W.make_attn_inputs(cfg, sess, 11)
+    bs = cfg.block_size
+    u = np.zeros(cfg.head_dim, dtype=np.float32)
+    u[:16] = 1.0                                   # |u|^2 = 16
+    enc = lambda x: W.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+    for s in range(sess.n_sessions):
+        P, N, a = int(sess.prefix_lens[s]), int(sess.new_lens[s]), int(sess.cu_new_lens[s])
+        total = P + N
+        for j in range(total):
+            t = j // 64
+            if shape == "rising":
+                amp = 2.0 * (t + 1)                # +32 * log2(e) = +46 powers of two per tile
+            elif shape == "falling":
+                amp = 2.0 * (total // 64 + 1 - t)
+            elif shape == "spike":
+                amp = 24.0 if j % 97 == 50 else 0.25 * (j % 5)     # isolated keys ~550 powers of two above the rest
+            else:
+                amp = 60.0 if j >= total - 3 else 0.5              # the last keys of the turn dwarf everything
+            row = enc(np.tile(u * amp, (cfg.n_kv_heads, 1)))
+            if j < P:
+                k_pool[sess.block_table[s, j // bs], j % bs] = row
+            else:
+                k_new[a + j - P] = row
+        q[a: a + N] = enc(np.tile(u, (N, cfg.n_q_heads, 1)))
+    check(oracle_mod, cfg, sess, (k_pool, v_pool, q, k_new, v_new), label=shape)
+
+
 def test_constant_values_per_session(oracle_mod):
     cfg = _cfg(n_sessions=6, prefix_dist=("uniform", 10, 200), new_dist=("uniform", 1, 50))
     sess = W.make_sessions(cfg, 8)
