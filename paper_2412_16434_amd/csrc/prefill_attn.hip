@@ -5,12 +5,15 @@
 //   * the G query heads that share a kv-head are stacked into the tile (128 query rows = G heads x 128/G tokens),
 //     so every K,V tile staged in LDS is reused by all of them;
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: the MFMA result layout then puts
-//     one query per lane, so the online-softmax statistics (running max, running sum, rescale factor) are per-lane
-//     scalars, and the bf16 probabilities a lane holds are exactly the B operand of O^T += V^T P^T;
+//     one query per lane, so the online-softmax state (reference, running sum) is per-lane scalars, and the bf16
+//     probabilities a lane holds are exactly the B operand of O^T += V^T P^T;
 //   * the row order in which K rows are fed to the MFMA is permuted so that the 8 probabilities a lane needs for
-//     one 16-key step of the second product are 8 consecutive keys, read from V^T in LDS with one 16-byte load;
-//   * K,V tiles of 64 keys are fetched from the paged pool (block-table indirection per 16-token block) or from
-//     the contiguous new-turn K,V, prefetched into registers while the previous tile is being multiplied.
+//     one 16-key step of the second product are 8 consecutive keys; the matching V^T operand comes from the
+//     transposing LDS read (ds_read_b64_tr_b16), V stays row-major in LDS;
+//   * K,V tiles of 64 keys go from the paged pool (block-table indirection per 16-token block) or from the
+//     contiguous new-turn K,V straight into LDS (global_load_lds_dwordx4), double-buffered, one tile ahead;
+//   * the softmax reference is stale on purpose (refreshed only when a row sum shows that it has to be), so no
+//     per-tile maximum and no per-tile rescaling of the accumulators.
 // generic path (fp32, or head_dim 64): one wave per query row, lanes over keys, fp32 online softmax.
 #include "common.h"
 
@@ -18,11 +21,10 @@
 
 #include <type_traits>
 
-// Development-only timing ablations (never defined in the product build): bit 0 skips the softmax arithmetic,
-// bit 1 the global loads and staging after the prologue, bit 2 the P*V product, bit 3 the Q*K product,
-// bit 4 the wait for the loads, bit 5 the barrier (results are then wrong; timing only), bit 6 records clocks.
-#ifndef SYMPH_DEV_ABLATE
-#define SYMPH_DEV_ABLATE 0
+// Development-only: -DSYMPH_DEV_TIMERS=1 makes workgroup 0 of the MFMA kernel record per-phase shader clocks of its
+// waves into the workspace header (it overwrites the page of zeros there: timing runs only, never the product build).
+#ifndef SYMPH_DEV_TIMERS
+#define SYMPH_DEV_TIMERS 0
 #endif
 
 namespace symph {
@@ -435,9 +437,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
   if (item_idx >= p.hdr[0]) return;
-#if SYMPH_DEV_ABLATE & (64 | 128)
-  const long long dev_c0 = clock64(), dev_w0 = wall_clock64();
-#endif
   const int kvh = blockIdx.x - item_idx * Hkv;
   const WorkItem it = p.items[item_idx];
   const int s = it.s;
@@ -579,7 +578,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) sc[kb][e] = 0.f;
-    if (!(SYMPH_DEV_ABLATE & 8)) {
+    {
       // the two 32-key blocks alternate, so consecutive MFMAs never wait for each other's accumulator
 #pragma unroll
       for (int st = 0; st < 8; ++st)
@@ -614,13 +613,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // accumulated so far has to be rescaled (0 for a first reference, 1 where nothing moved)
   auto raise_reference = [&](const f32x16 (&sc)[2], float& mb) {
     float mx = sc[0][0];
-    if (!(SYMPH_DEV_ABLATE & 1)) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
-      mx = max_across_halves(mx);
-    }
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
+    mx = max_across_halves(mx);
     const float m_new = fmaxf(m_run, mx * cs);
     // a row that has seen no key yet (a work item may start past its causal limit) keeps m_run = -inf, which the
     // merge step reads as "no contribution"; its exponent arguments use 0 so that they stay finite
@@ -636,8 +633,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   auto softmax_exp_half = [&](const f32x16& sc, float mb, bf16x8 (&pb)[2]) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      const float pv = (SYMPH_DEV_ABLATE & 1) ? sc[e] : __builtin_amdgcn_exp2f(fmaf(sc[e], cs, -mb));
-      pb[e >> 3][e & 7] = (__bf16)pv;
+      pb[e >> 3][e & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[e], cs, -mb));
     }
   };
   // row sum of the ROUNDED probabilities (the values the second product uses), two per instruction
@@ -667,32 +663,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     softmax_exp_half(sc[1], mb, pb[1]);
     ps = row_sum(pb);
   };
-  // O^T += V^T P^T on the matrix cores
-  auto pv = [&](const char* vbuf, const bf16x8 (&pb)[2][2]) {
-    if (SYMPH_DEV_ABLATE & 4) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) o_acc[kb][u] += (float)pb[kb][u][0] + (float)pb[kb][u][7];
-      return;
-    }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {  // the four d tiles alternate: independent accumulators back to back
-          const char* vp = vbuf + v_off[dt] + (8 * kb + 4 * u) * kGroupBytes;
-          const s16x4 lo = lds_read_tr16(reinterpret_cast<const __bf16*>(vp));
-          const s16x4 hi = lds_read_tr16(reinterpret_cast<const __bf16*>(vp + kGroupBytes));
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kb][u], o_acc[dt],
-                                                              0, 0, 0);
-        }
-  };
   auto wait_loads_and_sync = [&]() {
-    if (!(SYMPH_DEV_ABLATE & 16)) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's global->LDS loads have landed
-    if (!(SYMPH_DEV_ABLATE & 32)) __syncthreads();
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's global->LDS loads have landed
+    __syncthreads();
   };
 
   // Pipeline.  K(t) lives in K[t' & 1], V(t) in V[t' & 1] with t' = t - tile_begin.  Iteration j issues the loads
@@ -703,7 +676,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // A wave issues in order, so the instruction stream itself has to alternate between the two kinds; the
   // sched_group_barrier sequences ask the scheduler for that interleaving and for LDS reads that run several matrix
   // instructions ahead of their use (a read issued right before its MFMA exposes the full LDS latency every time).
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
   long long dev_ph[4] = {0, 0, 0, 0};
   const long long dev_c0 = clock64();
 #endif
@@ -735,10 +708,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     char* const v_other = PAR ? V0 : V1;  // held V(j-1), free now: receives V(j+1)
     f32x16 (&s_cur)[2] = PAR ? s_odd : s_even;   // S(j)
     f32x16 (&s_nxt)[2] = PAR ? s_even : s_odd;   // receives S(j+1)
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
     const long long ph0 = clock64();
 #endif
-    if (!(SYMPH_DEV_ABLATE & 2)) {
+    {
       if (j + 1 < tile_end) {
         int keep[4];
 #pragma unroll
@@ -749,7 +722,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       }
       if (j + 2 < tile_end) issue_tile(k_bytes, p.k_new, k_same, j + 2);
     }
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
     const long long ph1 = clock64();
 #endif
     // ---- block A
@@ -771,7 +744,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[kb][u]));
     asm volatile("" : "+v"(ps));
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
     asm volatile("s_nop 0" ::: "memory");
     const long long ph2 = clock64();
 #endif
@@ -801,8 +774,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
       for (int g = 0; g < 16; ++g) {
         if (g + 4 < 16) frag[g + 4] = v_frag(g + 4);
-        if (!(SYMPH_DEV_ABLATE & 4))
-          o_acc[g & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[g], pb[g >> 3][(g >> 2) & 1], o_acc[g & 3], 0, 0, 0);
+        o_acc[g & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[g], pb[g >> 3][(g >> 2) & 1], o_acc[g & 3], 0, 0, 0);
         pe[g] = __builtin_amdgcn_exp2f(fmaf(s_nxt[0][g], cs, -mb_cur));
         asm volatile("" : "+v"(pe[g]));  // evaluated in this slot (a value without side effects is otherwise placed
                                          // next to its use, after the last slot)
@@ -816,14 +788,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     pb[0][0] = pb_first[0];   // (garbage, and never used, when there was no tile j+1)
     pb[0][1] = pb_first[1];
     asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]));   // computed here, not after the barrier
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
     asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
     const long long ph3 = clock64();
 #endif
 #pragma unroll
     for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];      // the next V tile is j+2
     wait_loads_and_sync();
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
     const long long ph4 = clock64();
     dev_ph[0] += ph1 - ph0; dev_ph[1] += ph2 - ph1; dev_ph[2] += ph3 - ph2; dev_ph[3] += ph4 - ph3;
 #endif
@@ -840,26 +812,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     if (j + 1 < tile_end) step(j + 1, std::integral_constant<int, 1>{});
   }
 
-#if SYMPH_DEV_ABLATE & 256
+#if SYMPH_DEV_TIMERS
   if (blockIdx.x == 0 && (tid & 63) == 0) {  // per-phase shader clocks of each wave of workgroup 0
     long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16) + 8 * (tid >> 6);
     t[0] = dev_ph[0]; t[1] = dev_ph[1]; t[2] = dev_ph[2]; t[3] = dev_ph[3]; t[4] = clock64() - dev_c0; t[5] = tile_end - tile_begin;
-  }
-#endif
-#if SYMPH_DEV_ABLATE & 128
-  if (tid == 0) {  // per-workgroup timeline: start, end (100 MHz ticks), tiles, XCC/CU id; into the tail of the partials
-    long long* t = reinterpret_cast<long long*>(p.partials) + (1 << 23) + 4 * (long long)blockIdx.x;
-    unsigned hwid; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-    unsigned xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    t[0] = dev_w0; t[1] = wall_clock64(); t[2] = tile_end - tile_begin; t[3] = ((long long)xcc << 32) | hwid;
-  }
-#endif
-#if SYMPH_DEV_ABLATE & 64
-  if (blockIdx.x == 0 && tid == 0) {  // shader-clock ticks and 100 MHz ticks spent by workgroup 0
-    long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16);
-    t[0] = clock64() - dev_c0;
-    t[1] = wall_clock64() - dev_w0;
-    t[2] = tile_end - tile_begin;
   }
 #endif
   if (it.pslot < 0) {
