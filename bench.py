@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the readings of the plain
 # copy kernel of known size (profiles/bench_llama8b_hbm_traffic.md); other workloads have not been measured.
-MEASURED_TRAFFIC_BYTES = {"llama8b": {"kv_migrate": 17.22e9, "attn": 3.99e8}}
+MEASURED_TRAFFIC_BYTES = {"llama8b": {"kv_migrate": 17.22e9, "attn": 3.92e8}}
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
