@@ -38,8 +38,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama8b", help="workload name (default: the config the metric is quoted on)")
-    ap.add_argument("--only", choices=("all", "attn"), default="all",
-                    help="attn: time symph_prefix_prefill_attn alone on a one-layer cache (per-kernel profiles)")
+    ap.add_argument("--only", choices=("all", "attn", "resume"), default="all",
+                    help="attn: time symph_prefix_prefill_attn alone on a one-layer cache (per-kernel profiles); "
+                         "resume: the mixed-resume workload, attention on one stream beside the unpack of arriving "
+                         "sessions on a second stream (alone, alone, both)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the CPU-baseline leg")
@@ -147,6 +149,76 @@ def attn_only(args, cfg, sess):
                      "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}}))
 
 
+def resume_mix(args):
+    """Mixed resume (config 5): a batch of resumed turns (96 decode-shaped rows, 32 prefill turns) runs attention while
+    the K,V of 8 arriving sessions (32 layers, 4096 tokens each) are unpacked into another cache on a second stream.
+    Times attention alone, the unpack alone, and both released together: one JSON line."""
+    import torch
+    import paper_2412_16434_amd as S
+    import workloads as W
+    dev = "cuda:0"
+    acfg, ucfg = W.get_config("mixed_resume"), W.get_config("mixed_resume_incoming")
+    asess, usess = W.make_sessions(acfg), W.make_sessions(ucfg)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    kh, vh, qh, knh, vnh = W.make_attn_inputs(acfg, asess)
+    acache = S.KVCache(to_dev(kh)[None], to_dev(vh)[None])
+    q, k_new, v_new = to_dev(qh), to_dev(knh), to_dev(vnh)
+    out = torch.empty_like(q)
+    atable = torch.from_numpy(asess.block_table).to(dev)
+    aprefix = torch.from_numpy(asess.prefix_lens).to(dev)
+    cu = torch.from_numpy(asess.cu_new_lens).to(dev)
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(acache, asess.n_sessions, acfg.n_q_heads, asess.total_new_tokens,
+                                                     asess.max_new_len, asess.max_prefix_len)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    ushape = (ucfg.n_layers, ucfg.n_blocks, ucfg.block_size, ucfg.n_kv_heads, ucfg.head_dim)
+    uk = torch.zeros(ushape, dtype=torch.bfloat16, device=dev)
+    uv = torch.zeros(ushape, dtype=torch.bfloat16, device=dev)
+    ucache = S.KVCache(uk, uv)
+    utable = torch.from_numpy(usess.dst_block_table).to(dev)
+    uprefix = torch.from_numpy(usess.prefix_lens).to(dev)
+    uoff = torch.from_numpy(usess.buf_token_offsets).to(dev)
+    payload = S.kv_buffer_bytes(ucache, usess.total_prefix_tokens)
+    buf = torch.empty(payload // 2, dtype=torch.bfloat16, device=dev)
+    buf.view(torch.int16).fill_(0x3C00)
+    sa, su = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def attn():
+        S.prefix_prefill_attn(acache, 0, q, k_new, v_new, out, cu, aprefix, atable, asess.max_new_len,
+                              asess.max_prefix_len, acfg.scale, workspace=ws if ws_bytes else None, stream=sa)
+
+    def unpack():
+        S.kv_unpack(ucache, utable, uprefix, uoff, usess.total_prefix_tokens, buf, stream=su)
+
+    def timed(fns):
+        for f in fns:
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            for f in fns:
+                f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    for _ in range(args.warmup):
+        attn(); unpack()
+    torch.cuda.synchronize()
+    attn_ms, unpack_ms, both_ms = timed([attn]), timed([unpack]), timed([attn, unpack])
+    tflops = asess.attn_flops() / attn_ms / 1e9
+    print(json.dumps({
+        "metric": "mixed resume: prefix-prefill attn beside kv_unpack on a second stream", "value": both_ms, "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": both_ms, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "mixed_resume + mixed_resume_incoming", "attn_sessions": asess.n_sessions,
+                   "attn_new_tokens": asess.total_new_tokens, "attn_prefix_tokens": asess.total_prefix_tokens,
+                   "unpack_sessions": usess.n_sessions, "unpack_payload_bytes": payload},
+        "attn_alone": {"ms": attn_ms, "TFLOPs": tflops, "pct_mfma_bf16_peak": 100 * tflops / MFMA_BF16_PEAK_TFLOPS,
+                       "kv_GBps": asess.attn_bytes() / attn_ms / 1e6},
+        "unpack_alone": {"ms": unpack_ms, "GBps": 2.0 * payload / unpack_ms / 1e6,
+                         "pct_hbm_peak": 100 * 2.0 * payload / unpack_ms / 1e6 / HBM_PEAK_GBS},
+        "both": {"ms": both_ms, "sum_of_alone_ms": attn_ms + unpack_ms, "max_of_alone_ms": max(attn_ms, unpack_ms)}}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -163,6 +235,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.only == "resume":
+        resume_mix(args)
+        return
     cfg = W.get_config(args.config)
     if cfg.dtype != "bf16":
         print("bench.py: benchmark configs are bf16", file=sys.stderr)
