@@ -45,6 +45,9 @@ def _load():
         for fn in (lib.oracle_kv_pack, lib.oracle_kv_unpack):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp]
+        for fn in (lib.oracle_kv_pack_layers, lib.oracle_kv_unpack_layers):
+            fn.restype = C.c_int
+            fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp, i32, i32]
         lib.oracle_prefix_prefill_attn.restype = C.c_int
         lib.oracle_prefix_prefill_attn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
                                                    i32, i32, i32, f32, vp, i32, vp]
@@ -136,6 +139,42 @@ def kv_unpack(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_
                                   table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf))
     if rc != 0:
         raise RuntimeError("oracle_kv_unpack failed")
+
+
+def kv_pack_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+                   offsets: np.ndarray, buf: np.ndarray, layer_begin: int, layer_end: int) -> None:
+    """Gather layers ``layer_begin .. layer_end-1`` only into ``buf`` (whole-cache layout, modified in place)."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    buf = _check(buf, k_pool.dtype, "buf")
+    S = prefix_lens.shape[0]
+    if buf.size != int(offsets[S]) * 2 * L * hkv * d:
+        raise ValueError("buffer size does not match the sessions")
+    rc = _load().oracle_kv_pack_layers(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, _ptr(table),
+                                       table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf),
+                                       int(layer_begin), int(layer_end))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_pack_layers failed")
+
+
+def kv_unpack_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+                     offsets: np.ndarray, buf: np.ndarray, layer_begin: int, layer_end: int) -> None:
+    """Scatter layers ``layer_begin .. layer_end-1`` only of a migration buffer into the pools (in place)."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    buf = _check(buf, k_pool.dtype, "buf")
+    S = prefix_lens.shape[0]
+    if buf.size != int(offsets[S]) * 2 * L * hkv * d:
+        raise ValueError("buffer size does not match the sessions")
+    rc = _load().oracle_kv_unpack_layers(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, _ptr(table),
+                                         table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf),
+                                         int(layer_begin), int(layer_end))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_unpack_layers failed")
 
 
 def _attn_args(k_pool, v_pool, q, k_new, v_new, cu_new_lens, prefix_lens, table):

@@ -62,16 +62,19 @@ void oracle_kv_locate(int64_t layer_stride, int64_t block_stride, int32_t n_laye
   *buf_elem = (offsets[s] * 2 * n_layers + ((int64_t)2 * l + kv) * prefix_lens[s] + t) * row;
 }
 
+/* Layers layer_begin .. layer_end-1 only: the buffer keeps the layout of the whole cache (Sec. 3.3 moves K,V layer by
+ * layer; a layer of a session is one contiguous chunk of the layer-major buffer), everything else is not touched. */
 static int kv_copy(int to_buffer, void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride,
                    int32_t n_layers, int32_t block_size, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
                    const int32_t* table, int32_t table_stride, const int32_t* prefix_lens, const int64_t* offsets,
-                   int32_t n_sessions, void* buf) {
+                   int32_t n_sessions, void* buf, int32_t layer_begin, int32_t layer_end) {
   if (elem_bytes != 2 && elem_bytes != 4) return -1;
+  if (layer_begin < 0 || layer_end > n_layers || layer_begin > layer_end) return -1;
   const size_t row_bytes = (size_t)n_kv_heads * head_dim * elem_bytes;
   /* every (s, l) pair touches its own rows of the buffer and its own pool slots, so the pairs are independent */
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
   for (int32_t s = 0; s < n_sessions; ++s)
-    for (int32_t l = 0; l < n_layers; ++l)
+    for (int32_t l = layer_begin; l < layer_end; ++l)
       for (int32_t kv = 0; kv < 2; ++kv)
         for (int32_t t = 0; t < prefix_lens[s]; ++t) {
           int64_t pe, be;
@@ -93,7 +96,18 @@ int oracle_kv_pack(const void* k_base, const void* v_base, int64_t layer_stride,
                    const int32_t* table, int32_t table_stride, const int32_t* prefix_lens, const int64_t* offsets,
                    int32_t n_sessions, void* buf) {
   return kv_copy(1, (void*)k_base, (void*)v_base, layer_stride, block_stride, n_layers, block_size, n_kv_heads,
-                 head_dim, elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, buf);
+                 head_dim, elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, buf, 0, n_layers);
+}
+
+/* The gather restricted to layers layer_begin .. layer_end-1 (the rest of the buffer is left as it was). */
+int oracle_kv_pack_layers(const void* k_base, const void* v_base, int64_t layer_stride, int64_t block_stride,
+                          int32_t n_layers, int32_t block_size, int32_t n_kv_heads, int32_t head_dim,
+                          int32_t elem_bytes, const int32_t* table, int32_t table_stride, const int32_t* prefix_lens,
+                          const int64_t* offsets, int32_t n_sessions, void* buf, int32_t layer_begin,
+                          int32_t layer_end) {
+  return kv_copy(1, (void*)k_base, (void*)v_base, layer_stride, block_stride, n_layers, block_size, n_kv_heads,
+                 head_dim, elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, buf, layer_begin,
+                 layer_end);
 }
 
 /* Scatter: pools <- buffer, through the destination table.  Every pool byte that no valid token owns is left
@@ -103,7 +117,17 @@ int oracle_kv_unpack(void* k_base, void* v_base, int64_t layer_stride, int64_t b
                      const int32_t* table, int32_t table_stride, const int32_t* prefix_lens, const int64_t* offsets,
                      int32_t n_sessions, const void* buf) {
   return kv_copy(0, k_base, v_base, layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim,
-                 elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, (void*)buf);
+                 elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, (void*)buf, 0, n_layers);
+}
+
+/* The scatter restricted to layers layer_begin .. layer_end-1 (the other layers of the pools are left as they were). */
+int oracle_kv_unpack_layers(void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride, int32_t n_layers,
+                            int32_t block_size, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                            const int32_t* table, int32_t table_stride, const int32_t* prefix_lens,
+                            const int64_t* offsets, int32_t n_sessions, const void* buf, int32_t layer_begin,
+                            int32_t layer_end) {
+  return kv_copy(0, k_base, v_base, layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim,
+                 elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, (void*)buf, layer_begin, layer_end);
 }
 
 /* ------------------------------------------------------------------------------------------------------- */

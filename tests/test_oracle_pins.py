@@ -213,6 +213,61 @@ def test_unpack_round_trips_and_leaves_other_bytes_alone(oracle_mod, dtype):
             assert np.array_equal(vs[:, sess.dst_block_table[s, j], o], v_pool[:, sess.block_table[s, j], o])
 
 
+@pytest.mark.parametrize("lo,hi", [(0, 1), (1, 3), (2, 2), (0, 4), (3, 4)])
+def test_layer_range_pack_tagged_pool(oracle_mod, lo, hi):
+    """Layers lo..hi-1 only (Sec. 3.3: K,V travel layer by layer).  Tagged pools again: every buffer element of a
+    moved layer decodes to the coordinates the layout rules give, every other element keeps the sentinel it had, and a
+    layer of a session is ONE contiguous chunk of 2*P rows at (off[s]*2L + 2*layer*P) rows (closed form)."""
+    cfg = small_cfg("fp32", n_layers=4, n_sessions=4, prefix_dist=("uniform", 0, 23))
+    sess = W.make_sessions(cfg, 21)
+    k_pool, v_pool = tagged_pools(cfg)
+    H, d, bs, L = cfg.n_kv_heads, cfg.head_dim, cfg.block_size, cfg.n_layers
+    row = H * d
+    sentinel = np.uint32(0xFFFFFFFF)
+    buf = np.full(sess.payload_bytes() // 4, sentinel, dtype=np.uint32).view(np.float32)
+    oracle_mod.kv_pack_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, buf, lo, hi)
+    bits = buf.view(np.uint32)
+    kv, l, b, o, g, c = decode_tag(bits, cfg)
+    for s in range(sess.n_sessions):
+        P = int(sess.prefix_lens[s])
+        base = int(sess.buf_token_offsets[s]) * 2 * L * row
+        for layer in range(L):
+            chunk = slice(base + 2 * layer * P * row, base + 2 * (layer + 1) * P * row)
+            if not (lo <= layer < hi):
+                assert np.all(bits[chunk] == sentinel)
+                continue
+            assert np.all(l[chunk] == layer)
+            assert np.array_equal(kv[chunk], np.repeat([0, 1], P * row))
+            t = np.tile(np.repeat(np.arange(P), row), 2)
+            assert np.array_equal(b[chunk], sess.block_table[s][t // bs]) and np.array_equal(o[chunk], t % bs)
+            assert np.array_equal(g[chunk], np.tile(np.repeat(np.arange(H), d), 2 * P))
+            assert np.array_equal(c[chunk], np.tile(np.arange(d), 2 * P * H))
+
+
+def test_layer_ranges_compose_to_the_whole(oracle_mod):
+    """Disjoint layer ranges, in any order, give exactly the one-shot buffer / pools; an unpacked range leaves the
+    other layers of the pools untouched."""
+    cfg = small_cfg("bf16", n_layers=5, n_sessions=4, n_blocks=64, prefix_dist=("uniform", 0, 30))
+    sess = W.make_sessions(cfg, 22)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 22)
+    whole = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    buf = np.full_like(whole, 0x7FC1)
+    for lo, hi in [(3, 5), (0, 1), (1, 3)]:
+        oracle_mod.kv_pack_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, buf, lo, hi)
+    assert buf.tobytes() == whole.tobytes()
+
+    ref_k, ref_v = np.full_like(k_pool, 0x7FC1), np.full_like(v_pool, 0x7FC1)
+    oracle_mod.kv_unpack(ref_k, ref_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, whole)
+    got_k, got_v = np.full_like(k_pool, 0x7FC1), np.full_like(v_pool, 0x7FC1)
+    oracle_mod.kv_unpack_layers(got_k, got_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, whole, 1, 3)
+    assert np.all(got_k[[0, 3, 4]] == 0x7FC1) and np.all(got_v[[0, 3, 4]] == 0x7FC1)
+    assert got_k[1:3].tobytes() == ref_k[1:3].tobytes() and got_v[1:3].tobytes() == ref_v[1:3].tobytes()
+    for lo, hi in [(3, 5), (0, 1)]:
+        oracle_mod.kv_unpack_layers(got_k, got_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, whole,
+                                    lo, hi)
+    assert got_k.tobytes() == ref_k.tobytes() and got_v.tobytes() == ref_v.tobytes()
+
+
 def test_pack_preserves_nan_payloads_and_negative_zero(oracle_mod):
     cfg = small_cfg("bf16", n_sessions=2, n_layers=1, n_blocks=16, prefix_dist=("const", 7))
     sess = W.make_sessions(cfg, 5)
