@@ -97,6 +97,23 @@ int32_t symph_kv_unpack(const symph_kv_cache* cache, const int32_t* d_dst_block_
                         int64_t total_tokens, const void* d_buf, int64_t buf_bytes, void* stream);
 
 /*
+ * The same gather / scatter restricted to layers layer_begin .. layer_end-1 (Sec. 3.3: K,V are read and written layer
+ * by layer, asynchronously, so that a transfer overlaps the inference of the layers already there; a request whose
+ * lower layers have arrived can start).  The buffer keeps the layout and size of the whole cache: layer l of session
+ * s is the contiguous chunk of 2 * P_s rows (K then V) that starts (offsets[s] * 2 * L + 2 * l * P_s) rows into the
+ * buffer.  Buffer bytes of other layers (pack) and pool bytes of other layers (unpack) are not touched.
+ * 0 <= layer_begin <= layer_end <= n_layers; an empty range is SYMPH_OK with no launch.  Everything else as above.
+ */
+int32_t symph_kv_pack_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                             const int32_t* d_block_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                             const int64_t* d_buf_token_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
+                             int64_t buf_bytes, void* stream);
+int32_t symph_kv_unpack_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                               const int32_t* d_dst_block_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                               const int64_t* d_buf_token_offsets, int32_t n_sessions, int64_t total_tokens,
+                               const void* d_buf, int64_t buf_bytes, void* stream);
+
+/*
  * Prefix-cached prefill attention for one layer (Sec. 2.1: A_h = softmax(Q_h K_h^T * scale), y = concat_h A_h V_h;
  * "KV Cache": a token attends to all prior tokens).  For session s, query head h, new token i:
  *   out[cu[s]+i][h][:] = sum_j softmax_j(scale * <q, k_j>) v_j,   j over the P_s cached keys (paged, kv-head
@@ -137,6 +154,21 @@ int32_t symph_stage_to_host(void* h_pinned, const void* d_buf, int64_t bytes, vo
                             void* side_stream, void* event);
 int32_t symph_stage_to_device(void* d_buf, const void* h_pinned, int64_t bytes, void* consumer_stream,
                               void* side_stream, void* event);
+
+/*
+ * Host staging of ONE layer of every listed session (Sec. 3.3, layer-wise transfers): the n_sessions chunks of
+ * layer `layer` (see symph_kv_pack_layers for where they lie; same offsets in the pinned host buffer, which has the
+ * size of the whole device buffer) are copied on `side_stream`.  to_host: after everything already enqueued on
+ * `producer_stream`; to_device: `consumer_stream` then waits for the copies.  h_prefix_lens [n_sessions] and
+ * h_buf_token_offsets [n_sessions+1] are HOST arrays (the copies are sized on the host); row_bytes =
+ * n_kv_heads * head_dim * elem_bytes of the cache.  `event` as above.
+ */
+int32_t symph_stage_layer_to_host(void* h_pinned, const void* d_buf, const symph_kv_cache* cache, int32_t layer,
+                                  const int32_t* h_prefix_lens, const int64_t* h_buf_token_offsets,
+                                  int32_t n_sessions, void* producer_stream, void* side_stream, void* event);
+int32_t symph_stage_layer_to_device(void* d_buf, const void* h_pinned, const symph_kv_cache* cache, int32_t layer,
+                                    const int32_t* h_prefix_lens, const int64_t* h_buf_token_offsets,
+                                    int32_t n_sessions, void* consumer_stream, void* side_stream, void* event);
 
 /* Plain contiguous device copy with the same 16-byte-per-lane access shape as pack / unpack: the practical
  * HBM ceiling the migration kernels are compared with, and the known-size kernel used to calibrate hardware

@@ -12,10 +12,14 @@ from .binding import (  # noqa: F401
     kv_buffer_bytes,
     kv_pack,
     kv_unpack,
+    kv_pack_layers,
+    kv_unpack_layers,
     prefix_prefill_attn,
     prefix_prefill_attn_workspace_bytes,
     stage_to_host,
     stage_to_device,
+    stage_layer_to_host,
+    stage_layer_to_device,
     device_copy,
     status_string,
     EXPORTED_SYMBOLS,

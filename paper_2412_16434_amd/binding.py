@@ -14,9 +14,10 @@ _lib = None
 SYMPH_BF16, SYMPH_FP32 = 0, 1
 
 EXPORTED_SYMBOLS = (
-    "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_prefix_prefill_attn",
-    "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host", "symph_stage_to_device",
-    "symph_device_copy", "symph_status_string",
+    "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
+    "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
+    "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
+    "symph_status_string",
 )
 
 
@@ -52,6 +53,12 @@ def load_library():
     for fn in (lib.symph_kv_pack, lib.symph_kv_unpack):
         fn.restype = i32
         fn.argtypes = [cp, vp, i32, vp, vp, i32, i64, vp, i64, vp]
+    for fn in (lib.symph_kv_pack_layers, lib.symph_kv_unpack_layers):
+        fn.restype = i32
+        fn.argtypes = [cp, i32, i32, vp, i32, vp, vp, i32, i64, vp, i64, vp]
+    for fn in (lib.symph_stage_layer_to_host, lib.symph_stage_layer_to_device):
+        fn.restype = i32
+        fn.argtypes = [vp, vp, cp, i32, vp, vp, i32, vp, vp, vp]
     lib.symph_prefix_prefill_attn.restype = i32
     lib.symph_prefix_prefill_attn.argtypes = [cp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32,
                                               vp, i64, vp]
@@ -152,6 +159,27 @@ def kv_unpack(cache: KVCache, dst_block_table, prefix_lens, buf_token_offsets, t
                                           buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_unpack")
 
 
+def kv_pack_layers(cache: KVCache, layer_begin: int, layer_end: int, block_table, prefix_lens, buf_token_offsets,
+                   total_tokens: int, buf, stream=None) -> None:
+    """Gather layers ``layer_begin .. layer_end-1`` only into ``buf`` (whole-cache layout)."""
+    st = cache.struct()
+    _check(load_library().symph_kv_pack_layers(
+        C.byref(st), int(layer_begin), int(layer_end), _ptr(block_table),
+        block_table.shape[1] if block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
+        prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
+        "symph_kv_pack_layers")
+
+
+def kv_unpack_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block_table, prefix_lens,
+                     buf_token_offsets, total_tokens: int, buf, stream=None) -> None:
+    st = cache.struct()
+    _check(load_library().symph_kv_unpack_layers(
+        C.byref(st), int(layer_begin), int(layer_end), _ptr(dst_block_table),
+        dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
+        prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
+        "symph_kv_unpack_layers")
+
+
 def prefix_prefill_attn_workspace_bytes(cache: KVCache, n_sessions: int, n_q_heads: int, total_new_tokens: int,
                                         max_new_len: int, max_prefix_len: int) -> int:
     st = cache.struct()
@@ -183,6 +211,25 @@ def stage_to_device(d_buf, h_pinned, nbytes: int, consumer_stream, side_stream, 
     _check(load_library().symph_stage_to_device(_ptr(d_buf), _ptr(h_pinned), int(nbytes),
                                                 _stream_ptr(consumer_stream), _stream_ptr(side_stream),
                                                 _event_ptr(event)), "symph_stage_to_device")
+
+
+def stage_layer_to_host(h_pinned, d_buf, cache: KVCache, layer: int, h_prefix_lens, h_buf_token_offsets,
+                        producer_stream, side_stream, event) -> None:
+    """``h_prefix_lens`` (int32) and ``h_buf_token_offsets`` (int64) are HOST tensors (CPU, contiguous)."""
+    st = cache.struct()
+    _check(load_library().symph_stage_layer_to_host(
+        _ptr(h_pinned), _ptr(d_buf), C.byref(st), int(layer), _ptr(h_prefix_lens), _ptr(h_buf_token_offsets),
+        h_prefix_lens.shape[0], _stream_ptr(producer_stream), _stream_ptr(side_stream), _event_ptr(event)),
+        "symph_stage_layer_to_host")
+
+
+def stage_layer_to_device(d_buf, h_pinned, cache: KVCache, layer: int, h_prefix_lens, h_buf_token_offsets,
+                          consumer_stream, side_stream, event) -> None:
+    st = cache.struct()
+    _check(load_library().symph_stage_layer_to_device(
+        _ptr(d_buf), _ptr(h_pinned), C.byref(st), int(layer), _ptr(h_prefix_lens), _ptr(h_buf_token_offsets),
+        h_prefix_lens.shape[0], _stream_ptr(consumer_stream), _stream_ptr(side_stream), _event_ptr(event)),
+        "symph_stage_layer_to_device")
 
 
 def device_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -15,19 +15,58 @@ int32_t validate_cache(const symph_kv_cache* c) {
   return SYMPH_OK;
 }
 
-static int32_t migrate(bool pack, const symph_kv_cache* cache, const int32_t* d_table, int32_t table_stride,
-                       const int32_t* d_prefix_lens, const int64_t* d_offsets, int32_t n_sessions,
-                       int64_t total_tokens, void* d_buf, int64_t buf_bytes, void* stream) {
+static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                       const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                       const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
+                       int64_t buf_bytes, void* stream) {
   int32_t rc = validate_cache(cache);
   if (rc != SYMPH_OK) return rc;
   if (n_sessions < 0 || total_tokens < 0 || table_stride < 0 || buf_bytes < 0) return SYMPH_EINVAL;
-  if (n_sessions == 0 || total_tokens == 0) return SYMPH_OK;
+  if (layer_begin < 0 || layer_end > cache->n_layers || layer_begin > layer_end) return SYMPH_EINVAL;
+  if (n_sessions == 0 || total_tokens == 0 || layer_begin == layer_end) return SYMPH_OK;
   if (!d_table || !d_prefix_lens || !d_offsets || !d_buf || table_stride == 0) return SYMPH_EINVAL;
   const int64_t need = symph_kv_buffer_bytes(cache, total_tokens);
   if (need < 0) return SYMPH_EINVAL;
   if (buf_bytes < need) return SYMPH_EWORKSPACE;
-  return launch_kv_migrate(pack, cache, d_table, table_stride, d_prefix_lens, d_offsets, n_sessions, total_tokens,
-                           d_buf, buf_bytes, (hipStream_t)stream);
+  return launch_kv_migrate(pack, cache, layer_begin, layer_end, d_table, table_stride, d_prefix_lens, d_offsets,
+                           n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream);
+}
+
+// The chunk of one layer of one session in the migration buffer (bytes): 2 * P rows of K then V.
+static inline void layer_chunk(const symph_kv_cache* c, int32_t layer, int64_t offset_s, int32_t P, int64_t* begin,
+                               int64_t* bytes) {
+  const int64_t row_bytes = (int64_t)c->n_kv_heads * c->head_dim * elem_bytes_of(c->dtype);
+  *begin = (offset_s * 2 * c->n_layers + (int64_t)2 * layer * P) * row_bytes;
+  *bytes = (int64_t)2 * P * row_bytes;
+}
+
+static int32_t stage_layer(bool to_host, void* dst, const void* src, const symph_kv_cache* cache, int32_t layer,
+                           const int32_t* h_prefix_lens, const int64_t* h_offsets, int32_t n_sessions,
+                           void* other_stream, void* side_stream, void* event) {
+  int32_t rc = validate_cache(cache);
+  if (rc != SYMPH_OK) return rc;
+  if (layer < 0 || layer >= cache->n_layers || n_sessions < 0) return SYMPH_EINVAL;
+  if (n_sessions == 0) return SYMPH_OK;
+  if (!dst || !src || !h_prefix_lens || !h_offsets || !event || side_stream == other_stream) return SYMPH_EINVAL;
+  for (int32_t s = 0; s < n_sessions; ++s)
+    if (h_prefix_lens[s] < 0 || h_offsets[s] < 0 || h_offsets[s + 1] - h_offsets[s] < h_prefix_lens[s]) return SYMPH_EINVAL;
+  if (to_host) {  // the copies follow what the producer has enqueued so far
+    if (hipEventRecord((hipEvent_t)event, (hipStream_t)other_stream) != hipSuccess) return SYMPH_ELAUNCH;
+    if (hipStreamWaitEvent((hipStream_t)side_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
+  }
+  for (int32_t s = 0; s < n_sessions; ++s) {
+    int64_t begin, bytes;
+    layer_chunk(cache, layer, h_offsets[s], h_prefix_lens[s], &begin, &bytes);
+    if (bytes == 0) continue;
+    if (hipMemcpyAsync((char*)dst + begin, (const char*)src + begin, (size_t)bytes,
+                       to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, (hipStream_t)side_stream) != hipSuccess)
+      return SYMPH_ELAUNCH;
+  }
+  if (!to_host) {  // the consumer waits for the copies
+    if (hipEventRecord((hipEvent_t)event, (hipStream_t)side_stream) != hipSuccess) return SYMPH_ELAUNCH;
+    if (hipStreamWaitEvent((hipStream_t)other_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
+  }
+  return SYMPH_OK;
 }
 
 }  // namespace symph
@@ -46,15 +85,33 @@ int64_t symph_kv_buffer_bytes(const symph_kv_cache* cache, int64_t total_tokens)
 int32_t symph_kv_pack(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
                       const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets, int32_t n_sessions,
                       int64_t total_tokens, void* d_buf, int64_t buf_bytes, void* stream) {
-  return migrate(true, cache, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets, n_sessions,
-                 total_tokens, d_buf, buf_bytes, stream);
+  if (!cache) return SYMPH_EINVAL;
+  return migrate(true, cache, 0, cache->n_layers, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets,
+                 n_sessions, total_tokens, d_buf, buf_bytes, stream);
+}
+
+int32_t symph_kv_pack_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                             const int32_t* d_block_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                             const int64_t* d_buf_token_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
+                             int64_t buf_bytes, void* stream) {
+  return migrate(true, cache, layer_begin, layer_end, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets,
+                 n_sessions, total_tokens, d_buf, buf_bytes, stream);
 }
 
 int32_t symph_kv_unpack(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,
                         const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets, int32_t n_sessions,
                         int64_t total_tokens, const void* d_buf, int64_t buf_bytes, void* stream) {
-  return migrate(false, cache, d_dst_block_table, table_stride, d_prefix_lens, d_buf_token_offsets, n_sessions,
-                 total_tokens, const_cast<void*>(d_buf), buf_bytes, stream);
+  if (!cache) return SYMPH_EINVAL;
+  return migrate(false, cache, 0, cache->n_layers, d_dst_block_table, table_stride, d_prefix_lens,
+                 d_buf_token_offsets, n_sessions, total_tokens, const_cast<void*>(d_buf), buf_bytes, stream);
+}
+
+int32_t symph_kv_unpack_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                               const int32_t* d_dst_block_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                               const int64_t* d_buf_token_offsets, int32_t n_sessions, int64_t total_tokens,
+                               const void* d_buf, int64_t buf_bytes, void* stream) {
+  return migrate(false, cache, layer_begin, layer_end, d_dst_block_table, table_stride, d_prefix_lens,
+                 d_buf_token_offsets, n_sessions, total_tokens, const_cast<void*>(d_buf), buf_bytes, stream);
 }
 
 int64_t symph_prefix_prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
@@ -140,6 +197,20 @@ int32_t symph_stage_to_device(void* d_buf, const void* h_pinned, int64_t bytes, 
   if (hipEventRecord((hipEvent_t)event, (hipStream_t)side_stream) != hipSuccess) return SYMPH_ELAUNCH;
   if (hipStreamWaitEvent((hipStream_t)consumer_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
   return SYMPH_OK;
+}
+
+int32_t symph_stage_layer_to_host(void* h_pinned, const void* d_buf, const symph_kv_cache* cache, int32_t layer,
+                                  const int32_t* h_prefix_lens, const int64_t* h_buf_token_offsets,
+                                  int32_t n_sessions, void* producer_stream, void* side_stream, void* event) {
+  return stage_layer(true, h_pinned, d_buf, cache, layer, h_prefix_lens, h_buf_token_offsets, n_sessions,
+                     producer_stream, side_stream, event);
+}
+
+int32_t symph_stage_layer_to_device(void* d_buf, const void* h_pinned, const symph_kv_cache* cache, int32_t layer,
+                                    const int32_t* h_prefix_lens, const int64_t* h_buf_token_offsets,
+                                    int32_t n_sessions, void* consumer_stream, void* side_stream, void* event) {
+  return stage_layer(false, d_buf, h_pinned, cache, layer, h_prefix_lens, h_buf_token_offsets, n_sessions,
+                     consumer_stream, side_stream, event);
 }
 
 int32_t symph_device_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream) {

@@ -25,9 +25,10 @@ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 int32_t validate_cache(const symph_kv_cache* c);
 
 // Launchers (defined next to their kernels).
-int32_t launch_kv_migrate(bool pack, const symph_kv_cache* cache, const int32_t* d_table, int32_t table_stride,
-                          const int32_t* d_prefix_lens, const int64_t* d_offsets, int32_t n_sessions,
-                          int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream);
+int32_t launch_kv_migrate(bool pack, const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                          const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                          const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
+                          int64_t buf_bytes, hipStream_t stream);
 int32_t launch_device_copy(void* d_dst, const void* d_src, int64_t bytes, hipStream_t stream);
 
 struct AttnArgs {

@@ -28,6 +28,7 @@ struct MigrateParams {
   int32_t bs_shift;   // log2(block_size) when it is a power of two, else -1
   int32_t n_blocks;
   int32_t n_planes;  // 2 * n_layers
+  int32_t plane_begin, plane_end;  // planes moved by this launch (a range of layers: 2 * layer_begin .. 2 * layer_end)
   const int32_t* table;
   int32_t table_stride;
   const int32_t* prefix_lens;
@@ -104,17 +105,17 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   const int64_t pool_off = (int64_t)b * p.block_stride_b + (int64_t)slot * p.row_bytes + (int64_t)col * sizeof(VecT);
   const int64_t buf_off0 = sess_b + (int64_t)t * p.row_bytes + (int64_t)col * sizeof(VecT);
 
-  const int32_t plane0 = blockIdx.y * PLANES;
+  const int32_t plane0 = p.plane_begin + blockIdx.y * PLANES;
   VecT v[PLANES];
 #pragma unroll
   for (int i = 0; i < PLANES; ++i) {
-    const int32_t pl = min(plane0 + i, p.n_planes - 1);  // a ragged last group repeats its last plane (same bytes)
+    const int32_t pl = min(plane0 + i, p.plane_end - 1);  // a ragged last group repeats its last plane (same bytes)
     const char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
     v[i] = PACK ? load_vec<VecT, NT>(pool) : load_vec<VecT, NT>(p.buf + buf_off0 + pl * plane_b);
   }
 #pragma unroll
   for (int i = 0; i < PLANES; ++i) {
-    const int32_t pl = min(plane0 + i, p.n_planes - 1);
+    const int32_t pl = min(plane0 + i, p.plane_end - 1);
     char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
     if (PACK)
       store_vec<VecT, NT>(p.buf + buf_off0 + pl * plane_b, v[i]);
@@ -151,7 +152,7 @@ template <typename VecT, bool PACK>
 static int32_t launch_planes(int planes, int nt, const MigrateParams& p_in, hipStream_t stream) {
   const int64_t n_vec = p_in.total_tokens * p_in.vecs_per_row;
   const int64_t gx = ceil_div64(n_vec, 256);
-  const int64_t gy = ceil_div64(p_in.n_planes, planes);
+  const int64_t gy = ceil_div64(p_in.plane_end - p_in.plane_begin, planes);
   if (gx > 0x7FFFFFFFLL || gy > 65535) return SYMPH_EUNSUPPORTED;
   dim3 grid((unsigned)gx, (unsigned)gy);
   MigrateParams p = p_in;
@@ -172,9 +173,10 @@ static int32_t launch_planes(int planes, int nt, const MigrateParams& p_in, hipS
 
 static int log2_or_neg(int64_t x) { return (x > 0 && (x & (x - 1)) == 0) ? __builtin_ctzll((unsigned long long)x) : -1; }
 
-int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_table, int32_t table_stride,
-                          const int32_t* d_prefix_lens, const int64_t* d_offsets, int32_t n_sessions,
-                          int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream) {
+int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begin, int32_t layer_end,
+                          const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                          const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
+                          int64_t buf_bytes, hipStream_t stream) {
   const int eb = elem_bytes_of(c->dtype);
   const int64_t row_bytes = (int64_t)c->n_kv_heads * c->head_dim * eb;
   if (row_bytes > 0x7FFFFFFF) return SYMPH_EUNSUPPORTED;
@@ -198,6 +200,8 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_t
   p.bs_shift = log2_or_neg(c->block_size);
   p.n_blocks = c->n_blocks;
   p.n_planes = 2 * c->n_layers;
+  p.plane_begin = 2 * layer_begin;
+  p.plane_end = 2 * layer_end;
   p.table = d_table;
   p.table_stride = table_stride;
   p.prefix_lens = d_prefix_lens;
@@ -212,7 +216,7 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, const int32_t* d_t
   // lane repeats the session search for every vector, which only pays off while the search is short.
   int planes = env_int("SYMPH_MIGRATE_PLANES", (pack && n_sessions <= 64) ? 1 : 2);
   if (planes < 1 || planes > 8 || planes == 7) planes = 2;
-  while (planes > 1 && planes > p.n_planes) --planes;
+  while (planes > 1 && planes > p.plane_end - p.plane_begin) --planes;
   if (planes == 7) planes = 6;
   const int nt = env_int("SYMPH_MIGRATE_NT", 3);  // bit 0: non-temporal loads, bit 1: non-temporal stores
 

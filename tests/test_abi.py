@@ -72,6 +72,14 @@ def test_host_validation_rejects_without_launching():
     assert lib.symph_stage_to_host(None, 0x10, 16, None, 0x20, 0x30) == EINVAL
     assert lib.symph_stage_to_host(0x10, 0x10, 16, 0x20, 0x20, 0x30) == EINVAL     # side stream == producer
     assert lib.symph_stage_to_device(0x10, 0x10, 0, None, None, None) == 0
+    # layer ranges
+    assert lib.symph_kv_pack_layers(C.byref(good), 1, 1, 0x10, 4, 0x10, 0x10, 1, 16, 0x100, 1 << 30, None) == 0   # empty
+    assert lib.symph_kv_pack_layers(C.byref(good), -1, 1, 0x10, 4, 0x10, 0x10, 1, 16, 0x100, 1 << 30, None) == EINVAL
+    assert lib.symph_kv_unpack_layers(C.byref(good), 0, 3, 0x10, 4, 0x10, 0x10, 1, 16, 0x100, 1 << 30, None) == EINVAL
+    assert lib.symph_kv_unpack_layers(C.byref(good), 2, 1, 0x10, 4, 0x10, 0x10, 1, 16, 0x100, 1 << 30, None) == EINVAL
+    assert lib.symph_stage_layer_to_host(0x10, 0x10, C.byref(good), 2, 0x10, 0x10, 1, 0x20, 0x30, 0x40) == EINVAL  # layer
+    assert lib.symph_stage_layer_to_device(0x10, 0x10, C.byref(good), 0, 0x10, 0x10, 1, 0x20, 0x20, 0x40) == EINVAL
+    assert lib.symph_stage_layer_to_device(0x10, 0x10, C.byref(good), 0, None, None, 0, None, None, None) == 0
     assert lib.symph_device_copy(0x10, 0x20, 24, None) == EUNSUP
     assert lib.symph_device_copy(0x18, 0x20, 32, None) == EUNSUP
     assert S.status_string(0) == "ok" and "unsupported" in S.status_string(-2)

@@ -1,0 +1,126 @@
+"""Layer-wise migration (Symphony Sec. 3.3: K,V are read and written layer by layer, asynchronously, so that a transfer
+overlaps the inference of the layers already in place).
+
+* symph_kv_pack_layers / symph_kv_unpack_layers against the oracle's layer-range functions, bit for bit, including the
+  bytes that must NOT change;
+* a pipelined resume on three streams - host->device of layer l+1, unpack of layer l, attention on layer l-1 - must
+  leave exactly the pools of a one-shot unpack and give the attention outputs of the oracle for every layer.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_16434_amd as S
+import workloads as W
+from gpu_util import DEV, TOL, DeviceSessions, attn_errors, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _cfg(**kw):
+    base = dict(name="layerwise", index=40, dtype="bf16", n_layers=6, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                block_size=16, n_blocks=96, n_sessions=4, prefix_dist=("uniform", 0, 150), new_dist=("uniform", 1, 40),
+                sigma=1.0, scale=1.0 / np.sqrt(128.0))
+    base.update(kw)
+    return W.WorkloadConfig(**base)
+
+
+def sentinel_like(a):
+    out = np.empty_like(a)
+    out[...] = W.SENTINEL16
+    return out
+
+
+@pytest.mark.parametrize("lo,hi", [(0, 1), (5, 6), (2, 5), (0, 6), (3, 3)])
+def test_layer_range_pack_and_unpack(oracle_mod, lo, hi):
+    cfg = _cfg()
+    sess = W.make_sessions(cfg, 3)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 3)
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    n_elems = sess.payload_bytes() // 2
+    total = sess.total_prefix_tokens
+
+    ref_buf = np.full(n_elems, W.SENTINEL16, dtype=np.uint16)
+    oracle_mod.kv_pack_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, ref_buf, lo, hi)
+    buf = to_dev(np.full(n_elems, W.SENTINEL16, dtype=np.uint16))
+    S.kv_pack_layers(cache, lo, hi, ds.table, ds.prefix_lens, ds.offsets, total, buf)
+    torch.cuda.synchronize()
+    assert to_host(buf).tobytes() == ref_buf.tobytes(), "pack of a layer range differs from the oracle"
+
+    whole = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    ref_k, ref_v = sentinel_like(k_pool), sentinel_like(v_pool)
+    oracle_mod.kv_unpack_layers(ref_k, ref_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, whole, lo, hi)
+    dcache = S.KVCache(to_dev(sentinel_like(k_pool)), to_dev(sentinel_like(v_pool)))
+    S.kv_unpack_layers(dcache, lo, hi, ds.dst_table, ds.prefix_lens, ds.offsets, total, to_dev(whole))
+    torch.cuda.synchronize()
+    assert to_host(dcache.k_pool).tobytes() == ref_k.tobytes(), "unpack of a layer range: K pool differs"
+    assert to_host(dcache.v_pool).tobytes() == ref_v.tobytes(), "unpack of a layer range: V pool differs"
+
+
+def test_pipelined_resume_matches_one_shot_and_oracle(oracle_mod):
+    """The buffer of an arriving batch sits in pinned host memory.  Layer by layer: copy to the device (side stream),
+    unpack into fresh blocks (second stream), attention of the new turn on that layer (third stream), each step
+    released by the event of the one before it.  Every layer's attention output and the final pools are checked."""
+    cfg = _cfg(n_layers=5, n_sessions=5, prefix_dist=("uniform", 0, 260), new_dist=("uniform", 1, 50), n_blocks=256)
+    sess = W.make_sessions(cfg, 9)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 9)          # the source node's pools
+    L = cfg.n_layers
+    whole = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    ref_k, ref_v = sentinel_like(k_pool), sentinel_like(v_pool)
+    oracle_mod.kv_unpack(ref_k, ref_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, whole)
+    _, _, q, k_new, v_new = W.make_attn_inputs(W.scaled_config(cfg, n_layers=1), sess, 9)
+    ref_out = [oracle_mod.prefix_prefill_attn(ref_k[l], ref_v[l], q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                              sess.dst_block_table, cfg.scale) for l in range(L)]
+
+    ds = DeviceSessions(sess)
+    dcache = S.KVCache(to_dev(sentinel_like(k_pool)), to_dev(sentinel_like(v_pool)))
+    host = torch.from_numpy(whole.view(np.int16)).pin_memory()
+    dbuf = torch.full((whole.size,), 0x7FC1, dtype=torch.int16, device=DEV)
+    h_prefix, h_off = torch.from_numpy(sess.prefix_lens), torch.from_numpy(sess.buf_token_offsets)
+    qd, knd, vnd = to_dev(q), to_dev(k_new), to_dev(v_new)
+    outs = [torch.full_like(qd, float("nan")) for _ in range(L)]
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(dcache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
+                                                     sess.max_new_len, sess.max_prefix_len)
+    wss = [torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=DEV) for _ in range(L)]
+    s_copy, s_unpack, s_attn = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    ev_copy = [torch.cuda.Event() for _ in range(L)]
+    ev_unpack = [torch.cuda.Event() for _ in range(L)]
+    torch.cuda.synchronize()
+    for l in range(L):
+        S.stage_layer_to_device(dbuf, host, dcache, l, h_prefix, h_off, s_unpack, s_copy, ev_copy[l])
+        S.kv_unpack_layers(dcache, l, l + 1, ds.dst_table, ds.prefix_lens, ds.offsets, sess.total_prefix_tokens, dbuf,
+                           stream=s_unpack)
+        ev_unpack[l].record(s_unpack)
+        s_attn.wait_event(ev_unpack[l])
+        S.prefix_prefill_attn(dcache, l, qd, knd, vnd, outs[l], ds.cu_new_lens, ds.prefix_lens, ds.dst_table,
+                              sess.max_new_len, sess.max_prefix_len, cfg.scale, workspace=wss[l], stream=s_attn)
+    torch.cuda.synchronize()
+    assert to_host(dbuf.view(torch.bfloat16)).tobytes() == whole.tobytes(), "layer-wise host->device staging"
+    assert to_host(dcache.k_pool).tobytes() == ref_k.tobytes() and to_host(dcache.v_pool).tobytes() == ref_v.tobytes()
+    for l in range(L):
+        max_abs, rel = attn_errors(to_host(outs[l]), ref_out[l])
+        print(f"[pipelined resume] layer {l}: max_abs={max_abs:.3e} rel_l2={rel:.3e}", flush=True)
+        assert max_abs <= TOL["bf16"][0] and rel <= TOL["bf16"][1]
+
+
+def test_layer_wise_staging_to_host(oracle_mod):
+    """pack of layer l on one stream, device->host of that layer on the side stream, for every layer in turn."""
+    cfg = _cfg(n_layers=4, n_sessions=3)
+    sess = W.make_sessions(cfg, 4)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 4)
+    whole = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    dbuf = torch.zeros(whole.size, dtype=torch.int16, device=DEV)
+    host = torch.zeros(whole.size, dtype=torch.int16).pin_memory()
+    h_prefix, h_off = torch.from_numpy(sess.prefix_lens), torch.from_numpy(sess.buf_token_offsets)
+    s_pack, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+    evs = [torch.cuda.Event() for _ in range(cfg.n_layers)]
+    torch.cuda.synchronize()
+    for l in range(cfg.n_layers):
+        S.kv_pack_layers(cache, l, l + 1, ds.table, ds.prefix_lens, ds.offsets, sess.total_prefix_tokens, dbuf,
+                         stream=s_pack)
+        S.stage_layer_to_host(host, dbuf, cache, l, h_prefix, h_off, s_pack, s_copy, evs[l])
+    torch.cuda.synchronize()
+    assert host.numpy().view(np.uint16).tobytes() == whole.tobytes()
