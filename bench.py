@@ -38,10 +38,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama8b", help="workload name (default: the config the metric is quoted on)")
-    ap.add_argument("--only", choices=("all", "attn", "resume"), default="all",
+    ap.add_argument("--only", choices=("all", "attn", "resume", "pipeline"), default="all",
                     help="attn: time symph_prefix_prefill_attn alone on a one-layer cache (per-kernel profiles); "
                          "resume: the mixed-resume workload, attention on one stream beside the unpack of arriving "
-                         "sessions on a second stream (alone, alone, both)")
+                         "sessions on a second stream (alone, alone, both); pipeline: a resume whose buffer sits in "
+                         "pinned host memory, one shot against layer by layer on three streams")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the CPU-baseline leg")
@@ -219,6 +220,94 @@ def resume_mix(args):
         "both": {"ms": both_ms, "sum_of_alone_ms": attn_ms + unpack_ms, "max_of_alone_ms": max(attn_ms, unpack_ms)}}))
 
 
+def pipelined_resume(args, cfg, sess):
+    """A batch of turns resumes on this GPU while its K,V still sit in pinned host memory (Sec. 3.3).  One shot:
+    host->device of the whole buffer, unpack of all layers, attention layer after layer.  Layer-wise: copy of layer
+    l+1 (side stream), unpack of layer l (second stream) and attention on layer l-1 (third stream) overlap, each
+    released by the event of the step before.  Reference points: the copy alone (PCIe) and the attention of all
+    layers with K,V already in place.  One JSON line."""
+    import torch
+    import paper_2412_16434_amd as S
+    import workloads as W
+    dev = "cuda:0"
+    L, nb, bs = cfg.n_layers, cfg.n_blocks, cfg.block_size
+    k_pool = torch.zeros((L, nb, bs, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device=dev)
+    v_pool = torch.zeros_like(k_pool)
+    cache = S.KVCache(k_pool, v_pool)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    _, _, qh, knh, vnh = W.make_attn_inputs(cfg, sess)
+    q, k_new, v_new = to_dev(qh), to_dev(knh), to_dev(vnh)
+    out = torch.empty_like(q)
+    dst_table = torch.from_numpy(sess.dst_block_table).to(dev)
+    prefix_lens = torch.from_numpy(sess.prefix_lens).to(dev)
+    offsets = torch.from_numpy(sess.buf_token_offsets).to(dev)
+    cu = torch.from_numpy(sess.cu_new_lens).to(dev)
+    h_prefix, h_off = torch.from_numpy(sess.prefix_lens), torch.from_numpy(sess.buf_token_offsets)
+    total = sess.total_prefix_tokens
+    payload = S.kv_buffer_bytes(cache, total)
+    host = torch.empty(payload // 2, dtype=torch.int16, pin_memory=True)
+    host.fill_(0x3C00)
+    dbuf = torch.empty(payload // 2, dtype=torch.int16, device=dev)
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
+                                                     sess.max_new_len, sess.max_prefix_len)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    s_copy, s_unpack, s_attn = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    ev = torch.cuda.Event()
+    ev_copy = [torch.cuda.Event() for _ in range(L)]
+    ev_unpack = [torch.cuda.Event() for _ in range(L)]
+
+    def attn(l, stream):
+        S.prefix_prefill_attn(cache, l, q, k_new, v_new, out, cu, prefix_lens, dst_table, sess.max_new_len,
+                              sess.max_prefix_len, cfg.scale, workspace=ws if ws_bytes else None, stream=stream)
+
+    def copy_only():
+        S.stage_to_device(dbuf, host, payload, s_unpack, s_copy, ev)
+
+    def attn_only_all_layers():
+        for l in range(L):
+            attn(l, s_attn)
+
+    def one_shot():
+        S.stage_to_device(dbuf, host, payload, s_unpack, s_copy, ev)
+        S.kv_unpack(cache, dst_table, prefix_lens, offsets, total, dbuf, stream=s_unpack)
+        ev_unpack[0].record(s_unpack)
+        s_attn.wait_event(ev_unpack[0])
+        for l in range(L):
+            attn(l, s_attn)
+
+    def layer_wise():
+        for l in range(L):
+            S.stage_layer_to_device(dbuf, host, cache, l, h_prefix, h_off, s_unpack, s_copy, ev_copy[l])
+            S.kv_unpack_layers(cache, l, l + 1, dst_table, prefix_lens, offsets, total, dbuf, stream=s_unpack)
+            ev_unpack[l].record(s_unpack)
+            s_attn.wait_event(ev_unpack[l])
+            attn(l, s_attn)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(max(args.steps // 4, 3)):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        return float(np.median(ts))
+
+    copy_ms, attn_ms = timed(copy_only), timed(attn_only_all_layers)
+    shot_ms, wise_ms = timed(one_shot), timed(layer_wise)
+    print(json.dumps({
+        "metric": "resume from pinned host memory: host->device + unpack + attention of all layers", "value": wise_ms,
+        "unit": "ms", "n_gpus": 1, "steps": max(args.steps // 4, 3), "warmup": 1, "ms_per_step": wise_ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_sessions": sess.n_sessions, "n_layers": L, "payload_bytes": payload,
+                   "new_tokens": sess.total_new_tokens},
+        "host_to_device_alone": {"ms": copy_ms, "GBps": payload / copy_ms / 1e6},
+        "attention_all_layers_kv_in_place": {"ms": attn_ms},
+        "one_shot": {"ms": shot_ms, "after_the_copy_ms": shot_ms - copy_ms},
+        "layer_wise": {"ms": wise_ms, "after_the_copy_ms": wise_ms - copy_ms}}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -245,6 +334,9 @@ def main():
     sess = W.make_sessions(cfg)
     if args.only == "attn":
         attn_only(args, cfg, sess)
+        return
+    if args.only == "pipeline":
+        pipelined_resume(args, cfg, sess)
         return
 
     # ---- inputs, resident in HBM before anything is timed ------------------------------------------------
