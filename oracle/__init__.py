@@ -48,6 +48,8 @@ def _load():
         for fn in (lib.oracle_kv_pack_layers, lib.oracle_kv_unpack_layers):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp, i32, i32]
+        lib.oracle_kv_append.restype = C.c_int
+        lib.oracle_kv_append.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32]
         lib.oracle_prefix_prefill_attn.restype = C.c_int
         lib.oracle_prefix_prefill_attn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
                                                    i32, i32, i32, f32, vp, i32, vp]
@@ -175,6 +177,24 @@ def kv_unpack_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, 
                                          int(layer_begin), int(layer_end))
     if rc != 0:
         raise RuntimeError("oracle_kv_unpack_layers failed")
+
+
+def kv_append(k_pool: np.ndarray, v_pool: np.ndarray, layer: int, k_new: np.ndarray, v_new: np.ndarray,
+              cu_new_lens: np.ndarray, prefix_lens: np.ndarray, table: np.ndarray) -> None:
+    """Write the new turn's K,V rows of one layer into the pools (in place) behind each session's prefix."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    k_new = _check(k_new, k_pool.dtype, "k_new")
+    v_new = _check(v_new, k_pool.dtype, "v_new")
+    cu_new_lens = _check(cu_new_lens, np.int32, "cu_new_lens")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    table = _check(table, np.int32, "table")
+    if k_new.shape != v_new.shape or k_new.shape[1:] != (hkv, d) or int(cu_new_lens[-1]) != k_new.shape[0]:
+        raise ValueError("k_new / v_new shapes do not match the pool or cu_new_lens")
+    rc = _load().oracle_kv_append(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, int(layer), _ptr(k_new),
+                                  _ptr(v_new), _ptr(cu_new_lens), _ptr(prefix_lens), _ptr(table), table.shape[1],
+                                  prefix_lens.shape[0])
+    if rc != 0:
+        raise RuntimeError("oracle_kv_append failed")
 
 
 def _attn_args(k_pool, v_pool, q, k_new, v_new, cu_new_lens, prefix_lens, table):

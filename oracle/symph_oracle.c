@@ -130,6 +130,30 @@ int oracle_kv_unpack_layers(void* k_base, void* v_base, int64_t layer_stride, in
                  elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, (void*)buf, layer_begin, layer_end);
 }
 
+/* Append: the new turn's K,V rows of one layer go into the paged cache behind the session's prefix, so that the next
+ * turn (or decode step) finds them there (Sec. 2.1 "KV Cache": the keys and values of every processed token are kept;
+ * Sec. 3.3: a finished request's new K,V blocks join the session's cache).  Token i of session s has position
+ * P_s + i: block table[s][(P_s + i) / bs], slot (P_s + i) % bs.  Nothing else in the pools changes. */
+int oracle_kv_append(void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride, int32_t n_layers,
+                     int32_t block_size, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes, int32_t layer,
+                     const void* k_new, const void* v_new, const int32_t* cu_new_lens, const int32_t* prefix_lens,
+                     const int32_t* table, int32_t table_stride, int32_t n_sessions) {
+  if (elem_bytes != 2 && elem_bytes != 4) return -1;
+  if (layer < 0 || layer >= n_layers) return -1;
+  const int64_t row = (int64_t)n_kv_heads * head_dim;
+  const size_t row_bytes = (size_t)row * elem_bytes;
+  for (int32_t s = 0; s < n_sessions; ++s)
+    for (int32_t i = 0; i < cu_new_lens[s + 1] - cu_new_lens[s]; ++i) {
+      const int64_t pos = (int64_t)prefix_lens[s] + i;
+      const int64_t b = table[(int64_t)s * table_stride + pos / block_size];
+      const int64_t elem = (int64_t)layer * layer_stride + b * block_stride + (pos % block_size) * row;
+      const int64_t src = ((int64_t)cu_new_lens[s] + i) * row;
+      memcpy((char*)k_base + elem * elem_bytes, (const char*)k_new + src * elem_bytes, row_bytes);
+      memcpy((char*)v_base + elem * elem_bytes, (const char*)v_new + src * elem_bytes, row_bytes);
+    }
+  return 0;
+}
+
 /* ------------------------------------------------------------------------------------------------------- */
 
 static inline double widen(const void* base, int64_t idx, int is_bf16) {

@@ -268,6 +268,55 @@ def test_layer_ranges_compose_to_the_whole(oracle_mod):
     assert got_k.tobytes() == ref_k.tobytes() and got_v.tobytes() == ref_v.tobytes()
 
 
+def test_append_places_rows_by_position(oracle_mod):
+    """Appended K,V rows land at position P_s + i of their session (checked with tagged new rows and by reading the
+    pools back through the table, a numpy route), and every other element of the pools keeps its tag."""
+    cfg = small_cfg("fp32", n_layers=3, n_sessions=4, n_blocks=64, prefix_dist=("uniform", 0, 23), new_dist=("uniform", 0, 9))
+    sess = W.make_sessions(cfg, 31)
+    table = sess.table_with_room_for_the_new_turn()
+    k_pool, v_pool = tagged_pools(cfg)
+    k0, v0 = k_pool.copy(), v_pool.copy()
+    T, H, d, bs = sess.total_new_tokens, cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+    tag_new = lambda kv: (0x40000000 + (kv * T * H * d) + np.arange(T * H * d, dtype=np.uint32)).view(np.float32).reshape(T, H, d)
+    k_new, v_new = tag_new(0), tag_new(1)
+    layer = 1
+    oracle_mod.kv_append(k_pool, v_pool, layer, k_new, v_new, sess.cu_new_lens, sess.prefix_lens, table)
+    touched = np.zeros(k_pool.shape[:3], dtype=bool)
+    for s in range(sess.n_sessions):
+        P, a = int(sess.prefix_lens[s]), int(sess.cu_new_lens[s])
+        for i in range(int(sess.new_lens[s])):
+            pos = P + i
+            b, o = table[s, pos // bs], pos % bs
+            assert np.array_equal(k_pool[layer, b, o].view(np.uint32), k_new[a + i].view(np.uint32))
+            assert np.array_equal(v_pool[layer, b, o].view(np.uint32), v_new[a + i].view(np.uint32))
+            touched[layer, b, o] = True
+    assert np.array_equal(k_pool.view(np.uint32)[~touched], k0.view(np.uint32)[~touched])
+    assert np.array_equal(v_pool.view(np.uint32)[~touched], v0.view(np.uint32)[~touched])
+
+
+def test_append_then_attend_equals_attending_the_new_rows_directly(oracle_mod):
+    """The last token of a turn, computed (a) with the turn's K,V passed alongside the cache and (b) after appending
+    the turn's first N-1 tokens to the cache and passing only the last one, sees the same keys: same output row."""
+    cfg = small_cfg("fp32", n_layers=1, n_sessions=3, n_blocks=64, prefix_dist=("uniform", 0, 23), new_dist=("uniform", 2, 9))
+    sess = W.make_sessions(cfg, 32)
+    k_pool, v_pool, q, k_new, v_new = W.make_attn_inputs(cfg, sess, 32)
+    direct = oracle_mod.prefix_prefill_attn(k_pool, v_pool, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                            sess.block_table, cfg.scale)
+    table = sess.table_with_room_for_the_new_turn()
+    # append all but the last token of every session
+    head_rows = np.concatenate([np.arange(sess.cu_new_lens[s], sess.cu_new_lens[s + 1] - 1) for s in range(sess.n_sessions)])
+    last_rows = sess.cu_new_lens[1:] - 1
+    cu_head = np.zeros(sess.n_sessions + 1, np.int32)
+    cu_head[1:] = np.cumsum(sess.new_lens - 1)
+    kp, vp = k_pool[None].copy(), v_pool[None].copy()
+    oracle_mod.kv_append(kp, vp, 0, k_new[head_rows], v_new[head_rows], cu_head, sess.prefix_lens, table)
+    longer = (sess.prefix_lens + sess.new_lens - 1).astype(np.int32)
+    cu_one = np.arange(sess.n_sessions + 1, dtype=np.int32)
+    after = oracle_mod.prefix_prefill_attn(kp[0], vp[0], q[last_rows], k_new[last_rows], v_new[last_rows], cu_one, longer,
+                                           table, cfg.scale)
+    assert np.allclose(after, direct[last_rows], rtol=1e-12, atol=1e-14)
+
+
 def test_pack_preserves_nan_payloads_and_negative_zero(oracle_mod):
     cfg = small_cfg("bf16", n_sessions=2, n_layers=1, n_blocks=16, prefix_dist=("const", 7))
     sess = W.make_sessions(cfg, 5)

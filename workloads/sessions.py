@@ -54,6 +54,29 @@ class SessionBatch:
         return np.concatenate([tab[s, : nb[s]] for s in range(self.n_sessions)]) if self.n_sessions else \
             np.zeros(0, np.int32)
 
+    def table_with_room_for_the_new_turn(self, seed: int = 0) -> np.ndarray:
+        """The block table extended so that it also covers positions P_s .. P_s + N_s - 1: the extra blocks are
+        drawn (seeded, without replacement) from the blocks that no source or destination table lists."""
+        bs = self.cfg.block_size
+        need = (self.prefix_lens.astype(np.int64) + self.new_lens + bs - 1) // bs
+        have = self.blocks_per_session()
+        used = np.zeros(self.cfg.n_blocks, dtype=bool)
+        used[self.owned_blocks()] = True
+        if self.dst_block_table is not None:
+            used[self.owned_blocks(dst=True)] = True
+        free = np.random.default_rng(7000 + seed).permutation(np.nonzero(~used)[0]).astype(np.int32)
+        extra = int(np.sum(need - have))
+        if extra > free.size:
+            raise ValueError("pool too small to extend the tables")
+        table = np.full((self.n_sessions, max(int(need.max()) if need.size else 1, 1)), -1, dtype=np.int32)
+        at = 0
+        for s in range(self.n_sessions):
+            table[s, : have[s]] = self.block_table[s, : have[s]]
+            n = int(need[s] - have[s])
+            table[s, have[s]: have[s] + n] = free[at: at + n]
+            at += n
+        return table
+
     def payload_bytes(self) -> int:
         """Bytes of the migration buffer: K and V of every layer for every cached token."""
         return self.total_prefix_tokens * self.cfg.kv_bytes_per_token()
