@@ -410,6 +410,19 @@ def main():
     copy_ms = e0.elapsed_time(e1) / 5
     del scratch
 
+    # ---- append of the turn's K,V rows to the cache (one layer): small, outside the step, reported on its own ------
+    app_table = torch.from_numpy(sess.table_with_room_for_the_new_turn()).to(dev)
+    for _ in range(2):
+        S.kv_append(cache, la, k_new, v_new, cu, prefix_lens, app_table)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        S.kv_append(cache, la, k_new, v_new, cu, prefix_lens, app_table)
+    e1.record()
+    torch.cuda.synchronize()
+    append_us = e0.elapsed_time(e1) / 20 * 1e3
+    append_bytes = 2.0 * 2.0 * sess.total_new_tokens * cfg.n_kv_heads * cfg.head_dim * 2   # K and V, read + written
+
     # ---- host staging on a side stream (PCIe) -----------------------------------------------------------------
     staging = None
     if not args.no_staging:
@@ -459,6 +472,7 @@ def main():
                                 "pct_mfma_bf16_peak": 100 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                                 "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops},
         "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
+        "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,

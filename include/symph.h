@@ -114,6 +114,19 @@ int32_t symph_kv_unpack_layers(const symph_kv_cache* cache, int32_t layer_begin,
                                const void* d_buf, int64_t buf_bytes, void* stream);
 
 /*
+ * Append: write the new turn's K,V rows of one layer into the paged cache behind each session's prefix, so that the
+ * next turn or decode step finds them there (Sec. 2.1 "KV Cache": the keys and values of every processed token are
+ * kept; Sec. 3.3: the K,V a request produced join its session's cache).  Token i of session s has position P_s + i:
+ * block d_block_table[s][(P_s + i) / block_size], slot (P_s + i) % block_size; the table must list blocks for
+ * positions up to P_s + N_s - 1 (the caller takes them from its free list).  d_k_new / d_v_new
+ * [total_new_tokens][n_kv_heads][head_dim] in the cache dtype, d_cu_new_lens [n_sessions+1] int32.  Rows whose block
+ * id lies outside the cache are skipped; no other byte of the pools changes; the lengths are the caller's to update.
+ */
+int32_t symph_kv_append(const symph_kv_cache* cache, int32_t layer, const void* d_k_new, const void* d_v_new,
+                        const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens, const int32_t* d_block_table,
+                        int32_t table_stride, int32_t n_sessions, int32_t total_new_tokens, void* stream);
+
+/*
  * Prefix-cached prefill attention for one layer (Sec. 2.1: A_h = softmax(Q_h K_h^T * scale), y = concat_h A_h V_h;
  * "KV Cache": a token attends to all prior tokens).  For session s, query head h, new token i:
  *   out[cu[s]+i][h][:] = sum_j softmax_j(scale * <q, k_j>) v_j,   j over the P_s cached keys (paged, kv-head

@@ -15,6 +15,7 @@ SYMPH_BF16, SYMPH_FP32 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
+    "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
     "symph_status_string",
@@ -59,6 +60,8 @@ def load_library():
     for fn in (lib.symph_stage_layer_to_host, lib.symph_stage_layer_to_device):
         fn.restype = i32
         fn.argtypes = [vp, vp, cp, i32, vp, vp, i32, vp, vp, vp]
+    lib.symph_kv_append.restype = i32
+    lib.symph_kv_append.argtypes = [cp, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp]
     lib.symph_prefix_prefill_attn.restype = i32
     lib.symph_prefix_prefill_attn.argtypes = [cp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32,
                                               vp, i64, vp]
@@ -178,6 +181,15 @@ def kv_unpack_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block
         dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
         prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
         "symph_kv_unpack_layers")
+
+
+def kv_append(cache: KVCache, layer: int, k_new, v_new, cu_new_lens, prefix_lens, block_table, stream=None) -> None:
+    """Write the new turn's K,V rows of ``layer`` into the paged cache behind each session's prefix."""
+    st = cache.struct()
+    _check(load_library().symph_kv_append(
+        C.byref(st), int(layer), _ptr(k_new), _ptr(v_new), _ptr(cu_new_lens), _ptr(prefix_lens), _ptr(block_table),
+        block_table.shape[1] if block_table.dim() == 2 else 0, prefix_lens.shape[0], k_new.shape[0],
+        _stream_ptr(stream)), "symph_kv_append")
 
 
 def prefix_prefill_attn_workspace_bytes(cache: KVCache, n_sessions: int, n_q_heads: int, total_new_tokens: int,

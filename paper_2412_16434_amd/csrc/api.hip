@@ -114,6 +114,20 @@ int32_t symph_kv_unpack_layers(const symph_kv_cache* cache, int32_t layer_begin,
                  d_buf_token_offsets, n_sessions, total_tokens, const_cast<void*>(d_buf), buf_bytes, stream);
 }
 
+int32_t symph_kv_append(const symph_kv_cache* cache, int32_t layer, const void* d_k_new, const void* d_v_new,
+                        const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens, const int32_t* d_block_table,
+                        int32_t table_stride, int32_t n_sessions, int32_t total_new_tokens, void* stream) {
+  int32_t rc = validate_cache(cache);
+  if (rc != SYMPH_OK) return rc;
+  if (layer < 0 || layer >= cache->n_layers) return SYMPH_EINVAL;
+  if (n_sessions < 0 || total_new_tokens < 0 || table_stride < 0) return SYMPH_EINVAL;
+  if (n_sessions == 0 || total_new_tokens == 0) return SYMPH_OK;
+  if (!d_k_new || !d_v_new || !d_cu_new_lens || !d_prefix_lens || !d_block_table || table_stride == 0)
+    return SYMPH_EINVAL;
+  return launch_kv_append(cache, layer, d_k_new, d_v_new, d_cu_new_lens, d_prefix_lens, d_block_table, table_stride,
+                          n_sessions, total_new_tokens, (hipStream_t)stream);
+}
+
 int64_t symph_prefix_prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
                                                   int32_t total_new_tokens, int32_t max_new_len,
                                                   int32_t max_prefix_len) {

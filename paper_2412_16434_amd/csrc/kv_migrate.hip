@@ -226,6 +226,87 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begi
 }
 
 // ------------------------------------------------------------------------------------------------------------
+// append of the new turn's rows (one layer)
+// ------------------------------------------------------------------------------------------------------------
+struct AppendParams {
+  char* k_layer;  // the layer's K pool and V pool
+  char* v_layer;
+  int64_t block_stride_b;
+  int32_t row_bytes, vecs_per_row, block_size, n_blocks;
+  const char* k_new;
+  const char* v_new;
+  const int32_t* cu_new_lens;
+  const int32_t* prefix_lens;
+  const int32_t* table;
+  int32_t table_stride, n_sessions, total_new_tokens;
+};
+
+// One lane moves one vector of one new token's row, for K and for V.
+template <typename VecT>
+__global__ __launch_bounds__(256) void kv_append_kernel(const AppendParams p) {
+  const int64_t gv = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t tok = gv / p.vecs_per_row;
+  if (tok >= p.total_new_tokens) return;
+  const int32_t col = (int32_t)(gv - tok * p.vecs_per_row);
+  int32_t lo = 0, hi = p.n_sessions;  // last session with cu[s] <= tok (empty turns are skipped this way)
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (p.cu_new_lens[mid] <= tok)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  const int32_t s = lo;
+  const int64_t pos = (int64_t)p.prefix_lens[s] + (tok - p.cu_new_lens[s]);
+  if (pos < 0) return;
+  const int64_t j = pos / p.block_size;
+  if (j >= p.table_stride) return;
+  const int32_t b = p.table[(int64_t)s * p.table_stride + j];
+  if (b < 0 || b >= p.n_blocks) return;  // not a block of this cache: touch nothing
+  const int64_t dst = (int64_t)b * p.block_stride_b + (pos - j * p.block_size) * p.row_bytes + (int64_t)col * sizeof(VecT);
+  const int64_t src = tok * p.row_bytes + (int64_t)col * sizeof(VecT);
+  const VecT kv = *reinterpret_cast<const VecT*>(p.k_new + src);
+  const VecT vv = *reinterpret_cast<const VecT*>(p.v_new + src);
+  *reinterpret_cast<VecT*>(p.k_layer + dst) = kv;
+  *reinterpret_cast<VecT*>(p.v_layer + dst) = vv;
+}
+
+int32_t launch_kv_append(const symph_kv_cache* c, int32_t layer, const void* d_k_new, const void* d_v_new,
+                         const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens, const int32_t* d_table,
+                         int32_t table_stride, int32_t n_sessions, int32_t total_new_tokens, hipStream_t stream) {
+  const int eb = elem_bytes_of(c->dtype);
+  const int64_t row_bytes = (int64_t)c->n_kv_heads * c->head_dim * eb;
+  if (row_bytes > 0x7FFFFFFF) return SYMPH_EUNSUPPORTED;
+  AppendParams p;
+  p.k_layer = (char*)c->k_base + (int64_t)layer * c->layer_stride * eb;
+  p.v_layer = (char*)c->v_base + (int64_t)layer * c->layer_stride * eb;
+  p.block_stride_b = c->block_stride * eb;
+  const uintptr_t align_or = (uintptr_t)p.k_layer | (uintptr_t)p.v_layer | (uintptr_t)d_k_new | (uintptr_t)d_v_new |
+                             (uintptr_t)p.block_stride_b | (uintptr_t)row_bytes;
+  if (align_or & 3) return SYMPH_EUNSUPPORTED;
+  const int vec = (align_or & 15) ? 4 : 16;
+  p.row_bytes = (int32_t)row_bytes;
+  p.vecs_per_row = (int32_t)(row_bytes / vec);
+  p.block_size = c->block_size;
+  p.n_blocks = c->n_blocks;
+  p.k_new = (const char*)d_k_new;
+  p.v_new = (const char*)d_v_new;
+  p.cu_new_lens = d_cu_new_lens;
+  p.prefix_lens = d_prefix_lens;
+  p.table = d_table;
+  p.table_stride = table_stride;
+  p.n_sessions = n_sessions;
+  p.total_new_tokens = total_new_tokens;
+  const int64_t g = ceil_div64((int64_t)total_new_tokens * p.vecs_per_row, 256);
+  if (g > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
+  if (vec == 16)
+    hipLaunchKernelGGL(kv_append_kernel<u32x4>, dim3((unsigned)g), dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL(kv_append_kernel<unsigned int>, dim3((unsigned)g), dim3(256), 0, stream, p);
+  return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
+}
+
+// ------------------------------------------------------------------------------------------------------------
 // contiguous reference copy
 // ------------------------------------------------------------------------------------------------------------
 template <int UNROLL>

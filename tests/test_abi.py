@@ -80,6 +80,9 @@ def test_host_validation_rejects_without_launching():
     assert lib.symph_stage_layer_to_host(0x10, 0x10, C.byref(good), 2, 0x10, 0x10, 1, 0x20, 0x30, 0x40) == EINVAL  # layer
     assert lib.symph_stage_layer_to_device(0x10, 0x10, C.byref(good), 0, 0x10, 0x10, 1, 0x20, 0x20, 0x40) == EINVAL
     assert lib.symph_stage_layer_to_device(0x10, 0x10, C.byref(good), 0, None, None, 0, None, None, None) == 0
+    assert lib.symph_kv_append(C.byref(good), 2, 0x10, 0x10, 0x10, 0x10, 0x10, 4, 1, 8, None) == EINVAL           # layer
+    assert lib.symph_kv_append(C.byref(good), 0, None, 0x10, 0x10, 0x10, 0x10, 4, 1, 8, None) == EINVAL
+    assert lib.symph_kv_append(C.byref(good), 0, None, None, None, None, None, 0, 0, 0, None) == 0
     assert lib.symph_device_copy(0x10, 0x20, 24, None) == EUNSUP
     assert lib.symph_device_copy(0x18, 0x20, 32, None) == EUNSUP
     assert S.status_string(0) == "ok" and "unsupported" in S.status_string(-2)
