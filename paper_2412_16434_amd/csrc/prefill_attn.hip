@@ -22,7 +22,8 @@
 #include <type_traits>
 
 // Development-only: -DSYMPH_DEV_TIMERS=1 makes workgroup 0 of the MFMA kernel record per-phase shader clocks of its
-// waves into the workspace header (it overwrites the page of zeros there: timing runs only, never the product build).
+// waves into the workspace header (it overwrites the page of zeros there: timing runs only, never the product build),
+// and every workgroup a start / end record into an extra MiB at the end of the workspace.
 #ifndef SYMPH_DEV_TIMERS
 #define SYMPH_DEV_TIMERS 0
 #endif
@@ -146,7 +147,8 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const GenericParams p)
 // that re-read the same K,V share that XCD's L2.  Chunks of a split unit write unnormalised partial results
 // (running max, running sum, accumulators) to the workspace and a merge kernel combines them.
 struct WorkItem {   // 32 bytes
-  int32_t s, t0, tile_begin, tile_end, pslot, pad0, pad1, pad2;   // pslot < 0: whole unit, write the output directly
+  int32_t s, t0, tile_begin, tile_end, pslot;   // pslot < 0: whole unit, write the output directly
+  int32_t cu_s, n_new, n_prefix;                // of session s, so that a workgroup starts without looking them up
 };
 struct MergeItem {  // 16 bytes
   int32_t s, t0, pslot0, n_chunks;
@@ -311,7 +313,8 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     for (int ch = 0; ch < n_real; ++ch) {
       const int tb = ch * len, te = min(nt, tb + len);
       const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
-      if (pos < p.items_bound) p.items[pos] = WorkItem{s, t0, tb, te, pslot0 < 0 ? -1 : pslot0 + ch, 0, 0, 0};
+      if (pos < p.items_bound)
+        p.items[pos] = WorkItem{s, t0, tb, te, pslot0 < 0 ? -1 : pslot0 + ch, p.cu_new_lens[s], N, P};
     }
   }
   __syncthreads();
@@ -343,7 +346,32 @@ struct MfmaParams {
   const WorkItem* items;
   const MergeItem* merges;
   float* partials;
+#if SYMPH_DEV_TIMERS
+  long long* dev_trace;  // per workgroup: start, end (100 MHz counter), tiles, XCC and hardware id
+#endif
 };
+
+#if SYMPH_DEV_TIMERS
+// record of workgroup b (8 x 8 bytes): 0 start, 1 end (100 MHz counter), 2 shader clocks spent << 16 | tiles,
+// 3 XCC id << 32 | hardware id, 4 / 5 start of the main loop / of the epilogue (100 MHz counter)
+__device__ __forceinline__ void dev_trace_begin(const MfmaParams& p) {
+  if (threadIdx.x == 0) {
+    p.dev_trace[8 * blockIdx.x] = wall_clock64();
+    p.dev_trace[8 * blockIdx.x + 2] = clock64();
+  }
+}
+__device__ __forceinline__ void dev_trace_mark(const MfmaParams& p, int slot) {
+  if (threadIdx.x == 0) p.dev_trace[8 * blockIdx.x + slot] = wall_clock64();
+}
+__device__ __forceinline__ void dev_trace_end(const MfmaParams& p, int tiles) {
+  if (threadIdx.x == 0) {
+    long long* t = p.dev_trace + 8 * blockIdx.x;
+    t[1] = wall_clock64();
+    t[2] = ((clock64() - t[2]) << 16) | tiles;
+    t[3] = ((long long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+  }
+}
+#endif
 
 constexpr int kD = 128;  // head_dim
 // A row sum above this (one probability of 2^40 or more, or an overflow) makes the softmax reference stale.
@@ -436,14 +464,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
+  const WorkItem it = p.items[item_idx];  // the array covers the whole grid: read before the count is known
   if (item_idx >= p.hdr[0]) return;
   const int kvh = blockIdx.x - item_idx * Hkv;
-  const WorkItem it = p.items[item_idx];
+#if SYMPH_DEV_TIMERS
+  dev_trace_begin(p);
+#endif
   const int s = it.s;
   const int t0 = it.t0;
-  const int cu_s = p.cu_new_lens[s];
-  const int N = p.cu_new_lens[s + 1] - cu_s;
-  const int P = p.prefix_lens[s];
+  const int cu_s = it.cu_s;
+  const int N = it.n_new;
+  const int P = it.n_prefix;
   const int lb = LB ? LB : p.log_bs;
   const int bs_mask = (1 << lb) - 1;
 
@@ -502,10 +533,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   auto take_ids = [&]() {
 #pragma unroll
     for (int i = 0; i < 4; ++i) ids[i] = __builtin_amdgcn_readlane(ids_raw, i);
-  };
-  auto load_ids = [&](int tile) {
-    fetch_ids(tile);
-    take_ids();
   };
   // Issue the loads of one tile of K or of V into an LDS buffer.  Rows that do not exist (past the session's keys, or
   // named by a block id outside the cache) are read from the page of zeros, so they are finite and add nothing.
@@ -682,12 +709,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #endif
   f32x16 s_even[2], s_odd[2];  // scores of the even and of the odd tiles (counted from tile_begin)
   int ids_v[4];  // ids of the tile whose V rows are loaded next
-  load_ids(tile_begin);
-  issue_tile(k_bytes, p.k_new, K0, tile_begin);
-  issue_tile(v_bytes, p.v_new, V0, tile_begin);
-  if (tile_begin + 1 < tile_end) {
-    load_ids(tile_begin + 1);
-    issue_tile(k_bytes, p.k_new, K1, tile_begin + 1);
+  {
+    // the ids of the first two tiles with one load (lanes 0..7), before any K,V load is in flight
+    const int jb = (tile_begin * kBN + 16 * (lane & 7)) >> lb;
+    const int first8 = has_table ? table_row[min(jb, p.table_stride - 1)] : -1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ids[i] = __builtin_amdgcn_readlane(first8, i);
+    issue_tile(k_bytes, p.k_new, K0, tile_begin);
+    issue_tile(v_bytes, p.v_new, V0, tile_begin);
+    if (tile_begin + 1 < tile_end) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ids[i] = __builtin_amdgcn_readlane(first8, 4 + i);
+      issue_tile(k_bytes, p.k_new, K1, tile_begin + 1);
+    }
   }
   wait_loads_and_sync();
   qk(K0, s_even);
@@ -807,12 +841,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     fetch_ids(j + 3);   // index clamped to the table: harmless past the last tile
     iteration(j, par_c);
   };
+#if SYMPH_DEV_TIMERS
+  dev_trace_mark(p, 4);
+#endif
   for (int j = tile_begin; j < tile_end; j += 2) {
     step(j, std::integral_constant<int, 0>{});
     if (j + 1 < tile_end) step(j + 1, std::integral_constant<int, 1>{});
   }
 
 #if SYMPH_DEV_TIMERS
+  dev_trace_mark(p, 5);
   if (blockIdx.x == 0 && (tid & 63) == 0) {  // per-phase shader clocks of each wave of workgroup 0
     long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16) + 8 * (tid >> 6);
     t[0] = dev_ph[0]; t[1] = dev_ph[1]; t[2] = dev_ph[2]; t[3] = dev_ph[3]; t[4] = clock64() - dev_c0; t[5] = tile_end - tile_begin;
@@ -832,6 +870,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     part[64 * 256] = m_run;
     part[65 * 256] = l_run;
   }
+#if SYMPH_DEV_TIMERS
+  dev_trace_end(p, 2 * (tile_end - tile_begin));
+#endif
 }
 
 // Combine the chunks of a split unit: out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being the
@@ -919,6 +960,9 @@ static MfmaPlan make_plan(int32_t n_sessions, int32_t n_q_heads, int32_t n_kv_he
   pl.off_merges = align256(pl.off_items + (int64_t)pl.items_bound * sizeof(WorkItem));
   pl.off_partials = align256(pl.off_merges + (int64_t)pl.merges_bound * sizeof(MergeItem));
   pl.total_bytes = pl.off_partials + (int64_t)pl.pslots_bound * n_kv_heads * kPartialFloats * 4;
+#if SYMPH_DEV_TIMERS
+  pl.total_bytes = align256(pl.total_bytes) + (1 << 20);
+#endif
   return pl;
 }
 
@@ -1011,10 +1055,16 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.items = sp.items;
   p.merges = sp.merges;
   p.partials = (float*)(ws + pl.off_partials);
+#if SYMPH_DEV_TIMERS
+  p.dev_trace = (long long*)(ws + pl.total_bytes - (1 << 20));
+#endif
 
   const int64_t g_main = (int64_t)pl.items_bound * a.n_kv_heads;
   const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads * 4;
   if (g_main > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
+#if SYMPH_DEV_TIMERS
+  if (g_main * 64 > (1 << 20)) return SYMPH_EUNSUPPORTED;
+#endif
   // The scheduler keeps one table entry per session in LDS: larger batches run as consecutive slices of sessions
   // (same stream, same workspace; the bounds of the whole batch cover every slice).
   for (int32_t s0 = 0; s0 < a.n_sessions; s0 += kSchedMaxSessions) {
