@@ -423,6 +423,23 @@ def main():
     append_us = e0.elapsed_time(e1) / 20 * 1e3
     append_bytes = 2.0 * 2.0 * sess.total_new_tokens * cfg.n_kv_heads * cfg.head_dim * 2   # K and V, read + written
 
+    # ---- MFMA-only reference kernel: what the matrix cores deliver here, for a launch as short as the attention
+    # call (the shader clock is still ramping up) and sustained ------------------------------------------------------
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    mfma_ref = {}
+    for label, iters, reps in (("short", 300, 7), ("sustained", 40000, 3)):
+        ts = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = S.mfma_reference(iters, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms = float(np.median(ts))
+        mfma_ref[label] = {"ms": ms, "TFLOPs": flops / ms / 1e9, "pct_mfma_bf16_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS * 100}
+
     # ---- host staging on a side stream (PCIe) -----------------------------------------------------------------
     staging = None
     if not args.no_staging:
@@ -473,6 +490,7 @@ def main():
                                 "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops},
         "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
         "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
+        "mfma_reference": mfma_ref,
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,

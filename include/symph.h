@@ -188,6 +188,12 @@ int32_t symph_stage_layer_to_device(void* d_buf, const void* h_pinned, const sym
  * traffic counters.  bytes must be a multiple of 16, pointers 16-byte aligned. */
 int32_t symph_device_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
 
+/* Matrix-core reference: every wave of 2 * (number of CUs) workgroups of four waves runs 32 * iters dependent-free
+ * v_mfma_f32_32x32x16_bf16 instructions on registers (no memory traffic), the bf16 dense rate the attention kernel is
+ * compared with next to the published peak.  *h_flops (host, may be null) receives the floating-point operations of
+ * one launch; d_sink is a device word the kernel may write (it never does for finite inputs).  The caller times it. */
+int32_t symph_mfma_reference(int32_t iters, int64_t* h_flops, void* d_sink, void* stream);
+
 const char* symph_status_string(int32_t status);
 
 #ifdef __cplusplus

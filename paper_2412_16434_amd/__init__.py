@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     stage_layer_to_host,
     stage_layer_to_device,
     device_copy,
+    mfma_reference,
     status_string,
     EXPORTED_SYMBOLS,
 )

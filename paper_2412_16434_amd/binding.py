@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = (
     "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
+    "symph_mfma_reference",
     "symph_status_string",
 )
 
@@ -72,6 +73,8 @@ def load_library():
         fn.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.symph_device_copy.restype = i32
     lib.symph_device_copy.argtypes = [vp, vp, i64, vp]
+    lib.symph_mfma_reference.restype = i32
+    lib.symph_mfma_reference.argtypes = [i32, C.POINTER(C.c_int64), vp, vp]
     lib.symph_status_string.restype = C.c_char_p
     lib.symph_status_string.argtypes = [i32]
     _lib = lib
@@ -242,6 +245,14 @@ def stage_layer_to_device(d_buf, h_pinned, cache: KVCache, layer: int, h_prefix_
         _ptr(d_buf), _ptr(h_pinned), C.byref(st), int(layer), _ptr(h_prefix_lens), _ptr(h_buf_token_offsets),
         h_prefix_lens.shape[0], _stream_ptr(consumer_stream), _stream_ptr(side_stream), _event_ptr(event)),
         "symph_stage_layer_to_device")
+
+
+def mfma_reference(iters: int, sink, stream=None) -> int:
+    """Launch the MFMA-only reference kernel; returns the floating-point operations of the launch."""
+    flops = C.c_int64(0)
+    _check(load_library().symph_mfma_reference(int(iters), C.byref(flops), _ptr(sink), _stream_ptr(stream)),
+           "symph_mfma_reference")
+    return int(flops.value)
 
 
 def device_copy(dst, src, nbytes: int, stream=None) -> None:

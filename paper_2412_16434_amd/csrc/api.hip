@@ -235,6 +235,11 @@ int32_t symph_device_copy(void* d_dst, const void* d_src, int64_t bytes, void* s
   return launch_device_copy(d_dst, d_src, bytes, (hipStream_t)stream);
 }
 
+int32_t symph_mfma_reference(int32_t iters, int64_t* h_flops, void* d_sink, void* stream) {
+  if (iters <= 0 || !d_sink) return SYMPH_EINVAL;
+  return launch_mfma_reference(iters, h_flops, d_sink, (hipStream_t)stream);
+}
+
 const char* symph_status_string(int32_t status) {
   switch (status) {
     case SYMPH_OK: return "ok";

@@ -33,6 +33,7 @@ int32_t launch_kv_append(const symph_kv_cache* cache, int32_t layer, const void*
                          const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens, const int32_t* d_table,
                          int32_t table_stride, int32_t n_sessions, int32_t total_new_tokens, hipStream_t stream);
 int32_t launch_device_copy(void* d_dst, const void* d_src, int64_t bytes, hipStream_t stream);
+int32_t launch_mfma_reference(int32_t iters, int64_t* h_flops, void* d_sink, hipStream_t stream);
 
 struct AttnArgs {
   const void* k_layer;  // K pool of the chosen layer

@@ -1112,4 +1112,42 @@ int32_t launch_prefill_attn(const AttnArgs& a, hipStream_t stream) {
   return SYMPH_EUNSUPPORTED;
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// matrix-core reference: nothing but MFMAs on registers, four independent accumulators per wave
+// ------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void mfma_reference_kernel(int iters, float* sink) {
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(0.001f * (float)(threadIdx.x & 7));
+    b[e] = (__bf16)0.5f;
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t += acc[i][3];
+  if (t == -1.0f) *sink = t;  // sums of non-negative products: never taken, keeps the accumulators alive
+}
+
+int32_t launch_mfma_reference(int32_t iters, int64_t* h_flops, void* d_sink, hipStream_t stream) {
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return SYMPH_ELAUNCH;
+  if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+    return SYMPH_ELAUNCH;
+  const int n_wg = 2 * n_cu;
+  if (h_flops) *h_flops = (int64_t)n_wg * 4 * iters * 32 * (2LL * 32 * 32 * 16);
+  hipLaunchKernelGGL(mfma_reference_kernel, dim3((unsigned)n_wg), dim3(256), 0, stream, (int)iters, (float*)d_sink);
+  return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
+}
+
 }  // namespace symph

@@ -198,6 +198,16 @@ def test_device_copy_matches_source():
         assert torch.equal(dst[: n_bytes // 4], src[: n_bytes // 4]) and not dst[n_bytes // 4:].any()
 
 
+def test_mfma_reference_counts_its_work_and_leaves_the_sink_alone():
+    sink = torch.full((4,), 7.0, dtype=torch.float32, device=DEV)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    flops = S.mfma_reference(16, sink)
+    torch.cuda.synchronize()
+    # 2 workgroups per CU x 4 waves x 32 instructions per iteration x 2*32*32*16 operations each
+    assert flops == 2 * n_cu * 4 * 16 * 32 * 2 * 32 * 32 * 16
+    assert torch.equal(sink.cpu(), torch.full((4,), 7.0))
+
+
 # ---------------------------------------------------------------------------------------------------------
 # full sizes: counter-filled device pools, sampled rows against the oracle's index map, whole-pool properties
 # ---------------------------------------------------------------------------------------------------------
