@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama8b", help="workload name (default: the config the metric is quoted on)")
-    ap.add_argument("--only", choices=("all", "attn", "resume", "pipeline"), default="all",
+    ap.add_argument("--only", choices=("all", "attn", "resume", "pipeline", "decode"), default="all",
                     help="attn: time symph_prefix_prefill_attn alone on a one-layer cache (per-kernel profiles); "
                          "resume: the mixed-resume workload, attention on one stream beside the unpack of arriving "
                          "sessions on a second stream (alone, alone, both); pipeline: a resume whose buffer sits in "
@@ -148,6 +148,68 @@ def attn_only(args, cfg, sess):
                                 "kv_GBps": sess.attn_bytes() / ms / 1e6, "flops": sess.attn_flops()},
         "roofline": {"kernel": "attn_mfma", "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}}))
+
+
+def decode_step(args):
+    """A decode step: the 96 one-token rows of workload 5 (prefixes uniform in [512, 16384]) as a batch of their own.
+    Such a batch is HBM-bound (every K,V byte is used for G = 4 query rows), so the figure is K,V bytes per second
+    against the 8 TB/s peak; timed through the decode kernel (the default for such batches) and, with the switch off,
+    through the work-item kernel that mixed batches use."""
+    import torch
+    import paper_2412_16434_amd as S
+    import workloads as W
+    dev = "cuda:0"
+    cfg = W.get_config("mixed_resume")
+    sess = W.make_sessions(cfg)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    kh, vh, qh, knh, vnh = W.make_attn_inputs(cfg, sess)
+    cache = S.KVCache(to_dev(kh)[None], to_dev(vh)[None])
+    new_lens = np.diff(sess.cu_new_lens)
+    idx = np.nonzero(new_lens == 1)[0]
+    rows = sess.cu_new_lens[:-1][idx]                      # the one query row of each such session
+    q, k_new, v_new = (to_dev(np.ascontiguousarray(a[rows])) for a in (qh, knh, vnh))
+    out = torch.empty_like(q)
+    n = len(idx)
+    prefix_h = np.ascontiguousarray(sess.prefix_lens[idx])
+    prefix = torch.from_numpy(prefix_h).to(dev)
+    table = torch.from_numpy(np.ascontiguousarray(sess.block_table[idx])).to(dev)
+    cu = torch.arange(0, n + 1, dtype=torch.int32, device=dev)
+    max_prefix = int(prefix_h.max())
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, n, cfg.n_q_heads, n, 1, max_prefix)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    kv_bytes = float(prefix_h.sum() + n) * 2 * cfg.n_kv_heads * cfg.head_dim * 2
+
+    def timed():
+        for _ in range(max(args.warmup, 2)):
+            S.prefix_prefill_attn(cache, 0, q, k_new, v_new, out, cu, prefix, table, 1, max_prefix, cfg.scale, workspace=ws)
+        ts = []
+        for _ in range(args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            S.prefix_prefill_attn(cache, 0, q, k_new, v_new, out, cu, prefix, table, 1, max_prefix, cfg.scale, workspace=ws)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.median(ts)), out.clone()
+
+    dec_ms, dec_out = timed()
+    os.environ["SYMPH_ATTN_DECODE"] = "0"
+    main_ms, main_out = timed()
+    del os.environ["SYMPH_ATTN_DECODE"]
+    diff = float((dec_out.float() - main_out.float()).abs().max())
+    gbs = kv_bytes / dec_ms / 1e6
+    print(json.dumps({
+        "metric": "decode step: K,V GB/s of prefix-prefill attention on one-token rows, as % of HBM peak",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dec_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "mixed_resume, its 96 one-token rows as a batch", "n_sessions": n,
+                   "prefix_tokens": int(prefix_h.sum()), "kv_bytes": kv_bytes},
+        "decode_kernel": {"ms": dec_ms, "kv_GBps": gbs, "pct_hbm_peak": 100 * gbs / HBM_PEAK_GBS},
+        "work_item_kernel": {"ms": main_ms, "kv_GBps": kv_bytes / main_ms / 1e6,
+                             "pct_hbm_peak": 100 * kv_bytes / main_ms / 1e6 / HBM_PEAK_GBS},
+        "max_abs_difference_between_the_two": diff,
+        "roofline": {"kernel": "attn_decode", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None}}))
 
 
 def resume_mix(args):
@@ -327,6 +389,9 @@ def main():
     if args.only == "resume":
         resume_mix(args)
         return
+    if args.only == "decode":
+        decode_step(args)
+        return
     cfg = W.get_config(args.config)
     if cfg.dtype != "bf16":
         print("bench.py: benchmark configs are bf16", file=sys.stderr)
@@ -396,6 +461,10 @@ def main():
     pack_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     unpack_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     attn_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    spread = {name: {"median_ms": float(np.median(v)), "min_ms": float(np.min(v))}
+              for name, v in (("kv_pack", [e[0].elapsed_time(e[1]) for e in evs]),
+                              ("kv_unpack", [e[1].elapsed_time(e[2]) for e in evs]),
+                              ("prefix_prefill_attn", [e[2].elapsed_time(e[3]) for e in evs]))}
 
     # ---- contiguous copy of the same byte count: the practical HBM ceiling -------------------------------
     scratch = torch.empty_like(buf)
@@ -483,11 +552,14 @@ def main():
                    "n_kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "block_size": bs, "pool_blocks": nb,
                    "prefix_tokens": total, "new_tokens": sess.total_new_tokens, "payload_bytes": payload,
                    "step": "kv_pack(all layers) + kv_unpack(all layers) + prefix_prefill_attn(one layer)"},
-        "kv_pack": {"ms": pack_ms, "GBps": pack_gbs, "pct_hbm_peak": 100 * pack_gbs / HBM_PEAK_GBS},
-        "kv_unpack": {"ms": unpack_ms, "GBps": unpack_gbs, "pct_hbm_peak": 100 * unpack_gbs / HBM_PEAK_GBS},
+        "kv_pack": {"ms": pack_ms, "GBps": pack_gbs, "pct_hbm_peak": 100 * pack_gbs / HBM_PEAK_GBS,
+                    **spread["kv_pack"]},
+        "kv_unpack": {"ms": unpack_ms, "GBps": unpack_gbs, "pct_hbm_peak": 100 * unpack_gbs / HBM_PEAK_GBS,
+                      **spread["kv_unpack"]},
         "prefix_prefill_attn": {"ms": attn_ms, "TFLOPs": attn_tflops,
                                 "pct_mfma_bf16_peak": 100 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                                "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops},
+                                "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops,
+                                **spread["prefix_prefill_attn"]},
         "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
         "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
         "mfma_reference": mfma_ref,

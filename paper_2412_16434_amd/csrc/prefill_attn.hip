@@ -162,6 +162,9 @@ struct SchedParams {
   const int32_t* prefix_lens;
   int32_t n_sessions, bmt, n_kv_heads, target, target_slots, c_min, coarse_ok;
   int32_t items_bound, merges_bound, pslots_bound;
+  int32_t bmt_dec;      // sessions with at most this many new tokens go to the decode kernel (0: none do)
+  int32_t* dec_s;       // their indices, in session order
+  int32_t* dec_off;     // exclusive prefix sum of their key counts in 32-key tiles (one more entry: the total)
   int32_t* hdr;
   WorkItem* items;
   MergeItem* merges;
@@ -225,6 +228,30 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   }
   const int U = carry;
   if (tid == 0) unit_off[S] = U;
+  // Short turns (1 <= N_s <= bmt_dec) are not cut into work items: the decode kernel splits the concatenation of their
+  // key ranges evenly among its workgroups, and needs their indices and the prefix sum of their lengths for that.
+  int n_dec = 0, dec_total = 0;
+  if (p.bmt_dec > 0) {
+    for (int base = 0; base < S; base += kSchedThreads) {
+      const int s = base + tid;
+      int is_dec = 0, nt = 0;
+      if (s < S) {
+        const int N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
+        is_dec = N >= 1 && N <= p.bmt_dec;
+        nt = is_dec ? (p.prefix_lens[s] + N + 31) / 32 : 0;
+      }
+      int tot_c, tot_t;
+      const int ic = block_inclusive_scan(is_dec, wave_sums, tot_c);
+      const int itl = block_inclusive_scan(nt, wave_sums, tot_t);
+      if (is_dec) {
+        p.dec_s[n_dec + ic - 1] = s;
+        p.dec_off[n_dec + ic - 1] = dec_total + itl - nt;
+      }
+      n_dec += tot_c;
+      dec_total += tot_t;
+    }
+    if (tid == 0) p.dec_off[n_dec] = dec_total;
+  }
   __syncthreads();
   // unit u -> (session, first token, prefix length, new length)
   auto unit = [&](int u, int& s, int& t0, int& P, int& N) {
@@ -246,6 +273,7 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   for (int u = tid; u < U; u += kSchedThreads) {
     int s, t0, P, N;
     unit(u, s, t0, P, N);
+    if (N <= p.bmt_dec) continue;
     mine += (unsigned long long)unit_tiles(P, N, t0, p.bmt);
   }
   if (mine) atomicAdd(&total_tiles_s, mine);
@@ -253,7 +281,7 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   if (tid == 0) {
     // With at least two workgroup-sized units per slot, longest-first dispatch balances well without splitting
     // anything but the longest units; with fewer, every unit is cut so that there are about two pieces per slot.
-    const long long wg_units = (long long)U * p.n_kv_heads;
+    const long long wg_units = (long long)(U - n_dec) * p.n_kv_heads;
     const int target = (p.coarse_ok && wg_units >= 2ll * p.target_slots) ? p.target_slots : p.target;
     const unsigned long long tot = total_tiles_s * (unsigned long long)p.n_kv_heads;
     long long c = (long long)((tot + target - 1) / (unsigned long long)target);
@@ -272,6 +300,7 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   for (int u = tid; u < U; u += kSchedThreads) {
     int s, t0, P, N;
     unit(u, s, t0, P, N);
+    if (N <= p.bmt_dec) continue;
     const int nt = unit_tiles(P, N, t0, p.bmt);
     const int nc = (nt + C - 1) / C;
     const int len = (nt + nc - 1) / nc;
@@ -296,6 +325,7 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   for (int u = tid; u < U; u += kSchedThreads) {
     int s, t0, P, N;
     unit(u, s, t0, P, N);
+    if (N <= p.bmt_dec) continue;
     const int nt = unit_tiles(P, N, t0, p.bmt);
     const int nc = (nt + C - 1) / C;
     const int len = (nt + nc - 1) / nc;
@@ -323,6 +353,8 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     p.hdr[1] = C;
     p.hdr[2] = min(n_merge_s, p.merges_bound);
     p.hdr[3] = n_pslot_s;
+    p.hdr[4] = n_dec;
+    p.hdr[5] = dec_total;
   }
 }
 
@@ -344,8 +376,13 @@ struct MfmaParams {
   float scale_log2e;
   const int32_t* hdr;
   const WorkItem* items;
-  const MergeItem* merges;
+  MergeItem* merges;
   float* partials;
+  // attn_decode_kernel: the short turns' session indices and tile prefix sums (written by the scheduler), the first of
+  // its partial-result slots, and the room in the merge list
+  const int32_t* dec_s;
+  const int32_t* dec_off;
+  int32_t dec_pslot_base, merges_bound;
 #if SYMPH_DEV_TIMERS
   long long* dev_trace;  // per workgroup: start, end (100 MHz counter), tiles, XCC and hardware id
 #endif
@@ -354,18 +391,21 @@ struct MfmaParams {
 #if SYMPH_DEV_TIMERS
 // record of workgroup b (8 x 8 bytes): 0 start, 1 end (100 MHz counter), 2 shader clocks spent << 16 | tiles,
 // 3 XCC id << 32 | hardware id, 4 / 5 start of the main loop / of the epilogue (100 MHz counter)
-__device__ __forceinline__ void dev_trace_begin(const MfmaParams& p) {
+__device__ __forceinline__ void dev_trace_begin(const MfmaParams& p, int rec = -1) {
+  if (rec < 0) rec = blockIdx.x;
   if (threadIdx.x == 0) {
-    p.dev_trace[8 * blockIdx.x] = wall_clock64();
-    p.dev_trace[8 * blockIdx.x + 2] = clock64();
+    p.dev_trace[8 * rec] = wall_clock64();
+    p.dev_trace[8 * rec + 2] = clock64();
   }
 }
-__device__ __forceinline__ void dev_trace_mark(const MfmaParams& p, int slot) {
-  if (threadIdx.x == 0) p.dev_trace[8 * blockIdx.x + slot] = wall_clock64();
+__device__ __forceinline__ void dev_trace_mark(const MfmaParams& p, int slot, int rec = -1) {
+  if (rec < 0) rec = blockIdx.x;
+  if (threadIdx.x == 0) p.dev_trace[8 * rec + slot] = wall_clock64();
 }
-__device__ __forceinline__ void dev_trace_end(const MfmaParams& p, int tiles) {
+__device__ __forceinline__ void dev_trace_end(const MfmaParams& p, int tiles, int rec = -1) {
+  if (rec < 0) rec = blockIdx.x;
   if (threadIdx.x == 0) {
-    long long* t = p.dev_trace + 8 * blockIdx.x;
+    long long* t = p.dev_trace + 8 * rec;
     t[1] = wall_clock64();
     t[2] = ((clock64() - t[2]) << 16) | tiles;
     t[3] = ((long long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
@@ -441,6 +481,11 @@ constexpr int kTileBytes = 16 * kGroupBytes;  // 16640
 #define SYMPH_GLDS16(src, dst)                                                                       \
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),             \
                                    (__attribute__((address_space(3))) void*)(dst), 16, 0, 0)
+
+// The same with the non-temporal cache policy (bit 1 of the last operand): for rows that are read once
+#define SYMPH_GLDS16_NT(src, dst)                                                                    \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),             \
+                                   (__attribute__((address_space(3))) void*)(dst), 16, 0, 2)
 
 // One workgroup = one work item x one kv-head: 128 query rows (G heads x 128/G tokens) against the item's key tiles.
 // Requires block_size >= 16 (a power of two): the 16 consecutive key rows of a staging group then lie in ONE block, so
@@ -875,6 +920,379 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #endif
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Short turns (decode-like rows): a session whose new rows fit one wave (n_new * G <= 32) reads its whole K,V for
+// 32 query rows or fewer, so the work is moving K,V, not arithmetic.  One workgroup per (item, kv-head) again, but
+// the four waves split the KEYS: wave w takes the 32-key tiles u_begin + w, + 4, ... of the item, loads each into an
+// LDS buffer of its own (direct global->LDS loads) and runs without any barrier.  A wave only alternates between
+// "load a tile" and "use it", and using it is short, so what keeps HBM busy is the number of waves waiting for a
+// tile: two workgroups per CU, eight tiles (133 KiB) on their way per CU nearly all the time.  (Double buffers per
+// wave would halve the waves that fit, and a wave cannot keep a second, slower load in the background: loads return
+// in order.)  Same fragment layouts, same transposed scores and same stale-reference softmax as attn_mfma_kernel;
+// at the end the four partial results are combined through LDS.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int kSub = 32;                    // keys per tile of this kernel
+constexpr int kSubBytes = 8 * kGroupBytes;  // 8320
+constexpr int kDecWaveBytes = 2 * kSubBytes;  // K and V of one tile, per wave
+constexpr int kDecXchBytes = 4 * 66 * 64 * 4;  // exchange area at the end: per wave 64 accumulators, reference, sum per lane
+
+template <int G, int LB>
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p) {
+  constexpr int BMT = 128 / G;   // row mapping of the partial results (shared with the merge kernel)
+  constexpr int BMTD = 32 / G;   // query tokens this kernel covers per session
+  static_assert(kDecXchBytes >= 4 * kDecWaveBytes, "the exchange area holds the tile buffers");
+  __shared__ __attribute__((aligned(16))) char lds[kDecXchBytes];
+
+  // Even split: the short turns' key ranges, laid end to end, are cut into one equal range of 32-key tiles per
+  // workgroup (per kv-head), whatever the sessions' lengths.  A range covers the end of one session, whole sessions and
+  // the start of another: one segment each, processed one after the other.  A session that lies in one range is
+  // finished here; the pieces of one that spans several ranges go to the merge kernel.
+  const int Hkv = p.n_kv_heads;
+  const int wg = blockIdx.x / Hkv;
+  const int kvh = blockIdx.x - wg * Hkv;
+  const int n_dec = p.hdr[4];
+  const int total = p.hdr[5];
+  const int per_wg = (total + (int)(gridDim.x / Hkv) - 1) / (int)(gridDim.x / Hkv);
+  const int range_begin = wg * per_wg;
+  const int range_end = min(total, range_begin + per_wg);
+  if (range_begin >= range_end) return;
+#if SYMPH_DEV_TIMERS
+  dev_trace_begin(p, 8192 + blockIdx.x);  // the decode kernel's records follow the main kernel's
+#endif
+  const int lb = LB ? LB : p.log_bs;
+  const int bs_mask = (1 << lb) - 1;
+  const int tid = threadIdx.x;
+  int unit;  // last one that starts at or before range_begin
+  {
+    int lo = 0, hi = n_dec;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.dec_off[mid] <= range_begin)
+        lo = mid;
+      else
+        hi = mid;
+    }
+    unit = lo;
+  }
+  for (int pos = range_begin; pos < range_end; ++unit) {
+  const int unit_begin = p.dec_off[unit], unit_end = p.dec_off[unit + 1];
+  const int s = p.dec_s[unit];
+  const int cu_s = p.cu_new_lens[s];
+  const int N = p.cu_new_lens[s + 1] - cu_s;
+  const int P = p.prefix_lens[s];
+  const int u_begin = pos - unit_begin;                        // this segment: tiles [u_begin, u_end) of the session
+  const int u_end = min(range_end, unit_end) - unit_begin;
+  const bool whole = u_begin == 0 && u_end == unit_end - unit_begin;
+  const bool at_range_start = pos == range_begin;
+  pos = unit_begin + u_end;
+
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int n = lane & 31;
+  const int g2 = lane >> 5;
+  // every wave holds the same 32 query rows: row n = head n / BMTD, token n % BMTD
+  const int hh = n / BMTD;
+  const int tt = n - hh * BMTD;
+  const bool q_valid = tt < N;
+  const int head = kvh * G + hh;
+
+  bf16x8 qreg[8];
+  {
+    const __bf16* qp = p.q + ((int64_t)(cu_s + (q_valid ? tt : 0)) * p.n_q_heads + head) * kD + 8 * g2;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      qreg[st] = *reinterpret_cast<const bf16x8*>(qp + 16 * st);
+      if (!q_valid) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qreg[st][e] = (__bf16)0.0f;
+      }
+    }
+  }
+
+  const int total_keys = P + N;
+  const int fast_end = min(u_end, P / kSub);  // tiles below lie entirely inside the paged prefix
+
+  const bool has_table = p.table != nullptr && p.table_stride > 0;
+  const int32_t* table_row = p.table + (int64_t)s * p.table_stride;
+  const unsigned row_bytes = p.row_bytes;
+  // a wave loads all eight row groups of a tile: lane l fetches row l/16 of the group's four, logical 16-byte chunk
+  // (l % 16) ^ ((l/16) << 2)
+  const unsigned voff = (unsigned)(lane >> 4) * row_bytes + (unsigned)kvh * 256u +
+                        (unsigned)((lane & 15) ^ (((lane >> 4) & 3) << 2)) * 16u;
+  const char* k_bytes = reinterpret_cast<const char*>(p.k_layer);
+  const char* v_bytes = reinterpret_cast<const char*>(p.v_layer);
+  char* const my_lds = lds + wave * kDecWaveBytes;  // K, then V
+
+  // Ids of the two 16-row blocks of tile u (index clamped to the table); uniform addresses in read-only memory, so
+  // these are scalar loads that do not count among the vector loads the waits below wait for.
+  struct Ids {
+    int a, b;
+  };
+  auto fetch_ids = [&](int u) {
+    typedef const int32_t __attribute__((address_space(4))) * ConstTable;
+    ConstTable row = (ConstTable)(uintptr_t)table_row;
+    Ids r{-1, -1};
+    if (has_table) {
+      r.a = row[min((u * kSub) >> lb, p.table_stride - 1)];
+      r.b = row[min((u * kSub + 16) >> lb, p.table_stride - 1)];
+    }
+    return r;
+  };
+  // The K rows (which = 0) or the V rows (1) of tile u into this wave's buffer for them: eight loads
+  auto issue_half = [&](const int which, int u, const Ids ids) {
+    char* const buf = my_lds + which * kSubBytes;
+    const char* const pool = which ? v_bytes : k_bytes;
+    const bool fast = u < fast_end && max((unsigned)ids.a, (unsigned)ids.b) < (unsigned)p.n_blocks;
+    if (fast) {
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        uint64_t off = (uint64_t)(unsigned)(g < 4 ? ids.a : ids.b) * p.block_bytes + (uint64_t)(4 * (g & 3)) * row_bytes;
+        if (LB != 4) off += (uint64_t)((u * kSub + 16 * (g >> 2)) & bs_mask) * row_bytes;
+        SYMPH_GLDS16_NT(pool + off + voff, buf + g * kGroupBytes);  // every cached row is read once per kv-head
+      }
+    } else {
+      const unsigned in_row = (unsigned)kvh * 256u + (unsigned)((lane & 15) ^ (((lane >> 4) & 3) << 2)) * 16u;
+      const char* const zeros = reinterpret_cast<const char*>(p.hdr + kZeroPageInt) + (lane & 15) * 16;
+      const char* const fresh = reinterpret_cast<const char*>(which ? p.v_new : p.k_new);
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        const int key = u * kSub + 4 * g + (lane >> 4);
+        const unsigned bid = (unsigned)(g < 4 ? ids.a : ids.b);
+        const bool in_pool = key < P && (key >> lb) < p.table_stride && bid < (unsigned)p.n_blocks;
+        const bool in_new = key >= P && key < total_keys;
+        const char* src = zeros;
+        if (in_pool)
+          src = pool + (uint64_t)bid * p.block_bytes + (uint64_t)(key & bs_mask) * row_bytes + in_row;
+        else if (in_new)
+          src = fresh + (uint64_t)(cu_s + key - P) * row_bytes + in_row;
+        SYMPH_GLDS16(src, buf + g * kGroupBytes);
+      }
+    }
+  };
+
+  // ---- LDS reads: the fragment layouts of attn_mfma_kernel, for one 32-key block
+  const int krow = key_of_row(n);
+  const int k_lane = (krow >> 2) * kGroupBytes + (krow & 3) * 256 + g2 * 16;
+  int k_off[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) k_off[q] = k_lane + 64 * (q ^ (krow & 3));
+  const int i16 = lane & 15;
+  const int vrow = 8 * g2 + (i16 >> 2);
+  const int v_lane = (vrow >> 2) * kGroupBytes + (vrow & 3) * 256 + 32 * ((lane >> 4) & 1) + 8 * (i16 & 3);
+  int v_off[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) v_off[dt] = v_lane + 64 * (dt ^ (vrow & 3));
+
+  f32x16 o_acc[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[dt][e] = 0.f;
+  float m_run = -INFINITY;  // softmax reference in log2 units, -inf: no key seen yet
+  float mb = 0.f;           // the same, finite
+  float l_run = 0.f;
+  const float cs = p.scale_log2e;
+  const int q_limit = P + tt;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+  auto exps = [&](const f32x16& sc, bf16x8 (&pb)[2]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) pb[e >> 3][e & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[e], cs, -mb));
+    float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8 v = pb[u];
+      ps0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[0], v[1]}, ones, ps0, false);
+      ps1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[2], v[3]}, ones, ps1, false);
+      ps0 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[4], v[5]}, ones, ps0, false);
+      ps1 = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{v[6], v[7]}, ones, ps1, false);
+    }
+    return ps0 + ps1;
+  };
+  // reference := max(reference, maximum of this tile); everything accumulated so far is rescaled
+  auto raise_reference = [&](const f32x16& sc) {
+    float mx = sc[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[e]);
+    mx = max_across_halves(mx);
+    const float m_new = fmaxf(m_run, mx * cs);
+    const float a = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    mb = (m_new == -INFINITY) ? 0.f : m_new;
+    l_run *= a;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o_acc[dt][e] *= a;
+  };
+
+  bf16x8 pb[2];  // the tile's probabilities, from scores_of_tile to values_of_tile
+  auto scores_of_tile = [&](const int u, const bool first) {
+    const char* const kb_cur = my_lds;
+    // ---- S^T = K Q^T
+    f32x16 sc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sc[e] = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      const bf16x8 frag = *reinterpret_cast<const bf16x8*>(kb_cur + k_off[g >> 1] + 32 * (g & 1));
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag, qreg[g], sc, 0, 0, 0);
+    }
+    // causal mask: only tiles that reach past the first query's limit
+    if (u * kSub + kSub - 1 > P) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = u * kSub + 16 * (e >> 3) + 8 * g2 + (e & 7);
+        if (key > q_limit) sc[e] = -INFINITY;
+      }
+    }
+    // ---- probabilities against the (stale) reference
+    if (first) raise_reference(sc);
+    float ps = exps(sc, pb);
+    if (__any(!(ps <= kRefreshSum) || (m_run == -INFINITY && ps > 0.f))) {
+      raise_reference(sc);
+      ps = exps(sc, pb);
+    }
+    l_run += ps;
+  };
+  auto values_of_tile = [&]() {
+    const char* const vb_cur = my_lds + kSubBytes;
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const char* vp = vb_cur + v_off[dt] + 4 * ks * kGroupBytes;
+        const s16x4 lo = lds_read_tr16(reinterpret_cast<const __bf16*>(vp));
+        const s16x4 hi = lds_read_tr16(reinterpret_cast<const __bf16*>(vp + kGroupBytes));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[ks], o_acc[dt], 0, 0, 0);
+      }
+  };
+
+  // ---- this wave's tiles: u_begin + wave, + 4, ...; no barrier: the buffers are the wave's own.  The K buffer is
+  // refilled with the next tile's rows as soon as the scores are done, the V buffer as soon as the values are, so
+  // one of the two is always on its way while the other is used.  Loads return in order: "all but the last eight"
+  // is exactly the older of the two halves.
+  {
+    bool first = true;
+    int u = u_begin + wave;
+    Ids ids = fetch_ids(u);
+    if (u < u_end) {
+      issue_half(0, u, ids);
+      issue_half(1, u, ids);
+    }
+#if SYMPH_DEV_TIMERS
+    long long dev_t[3] = {0, 0, 0};
+    int dev_n = 0;
+#endif
+    for (; u < u_end; u += 4) {
+      const bool more = u + 4 < u_end;
+      const Ids ids_next = fetch_ids(u + 4);
+#if SYMPH_DEV_TIMERS
+      const long long c0 = clock64();
+#endif
+      __builtin_amdgcn_s_waitcnt(0x0F70 | 8);  // vmcnt(8): K(u) has landed, V(u) may be on its way
+      asm volatile("" ::: "memory");
+#if SYMPH_DEV_TIMERS
+      const long long c1 = clock64();
+#endif
+      scores_of_tile(u, first);
+      first = false;
+      asm volatile("" ::: "memory");
+      if (more) issue_half(0, u + 4, ids_next);
+      if (more)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | 8);  // V(u) has landed, K(u+4) may be on its way
+      else
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+      asm volatile("" ::: "memory");
+      values_of_tile();
+      asm volatile("" ::: "memory");
+      if (more) issue_half(1, u + 4, ids_next);
+#if SYMPH_DEV_TIMERS
+      asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
+      const long long c3 = clock64();
+      dev_t[1] += c1 - c0; dev_t[2] += c3 - c1; ++dev_n;
+#endif
+    }
+#if SYMPH_DEV_TIMERS
+    if (blockIdx.x == 8 * 5 && lane == 0) {  // one workgroup: per-wave clocks spent waiting for K, and on the rest
+      long long* t = p.dev_trace + (1 << 17) - 64 + 8 * wave;
+      t[0] = dev_t[0]; t[1] = dev_t[1]; t[2] = dev_t[2]; t[3] = dev_n;
+    }
+#endif
+  }
+
+  // ---- combine the four waves: wave w ends up with the d-slice 32w .. 32w+31 of the 32 rows
+  __syncthreads();  // every wave is done with its tiles: the buffers become the exchange area
+  float* const xch = reinterpret_cast<float*>(lds);  // [wave][66][64]: 64 accumulators, reference, sum per lane
+  {
+    float* mine = xch + wave * 66 * 64 + lane;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mine[(dt * 16 + e) * 64] = o_acc[dt][e];
+    mine[64 * 64] = m_run;
+    mine[65 * 64] = l_run;
+  }
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) M = fmaxf(M, xch[(v * 66 + 64) * 64 + lane]);
+  float acc[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  float L = 0.f;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const float* src = xch + v * 66 * 64 + lane;
+    const float mv = src[64 * 64];
+    const float w = (mv == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mv - M);
+    L += w * src[65 * 64];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = fmaf(w, src[(wave * 16 + e) * 64], acc[e]);
+  }
+  if (whole) {
+    const float l_tot = sum_across_halves(L);
+    if (q_valid) {
+      const float inv = 1.0f / l_tot;
+      __bf16* op = p.out + ((int64_t)(cu_s + tt) * p.n_q_heads + head) * kD + 32 * wave + 4 * g2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bf16x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (__bf16)(acc[4 * i + j] * inv);
+        *reinterpret_cast<bf16x4*>(op + 8 * i) = v;
+      }
+    }
+  } else {
+    // Two slots per workgroup: 2 * wg for a segment that starts where the range starts (a session continued from
+    // the range before), 2 * wg + 1 for one that starts inside it.  The pieces of a session are then its first one
+    // and, for every further range it reaches into, that range's even slot; the workgroup that has the first piece
+    // puts the session on the merge list (negative count: this slot rule).
+    const int pslot = p.dec_pslot_base + 2 * wg + (at_range_start ? 0 : 1);
+    if (u_begin == 0 && kvh == 0 && tid == 0) {
+      const int last_wg = (unit_end - 1) / per_wg;
+      const int mi = atomicAdd(const_cast<int32_t*>(p.hdr) + 2, 1);
+      if (mi < p.merges_bound) p.merges[mi] = MergeItem{s, 0, pslot, -(last_wg - wg + 1)};
+    }
+    // the merge kernel's layout: thread (row >> 5) * 64 + g2 * 32 + (row & 31) with row = head * BMT + token
+    const int row = hh * BMT + tt;
+    float* part = p.partials + ((int64_t)pslot * Hkv + kvh) * kPartialFloats + (row >> 5) * 64 + g2 * 32 + (row & 31);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) part[(wave * 16 + e) * 256] = acc[e];
+    if (wave == 0) {
+      part[64 * 256] = M;
+      part[65 * 256] = L;
+    }
+  }
+  __syncthreads();  // the exchange area becomes tile buffers again
+  }
+#if SYMPH_DEV_TIMERS
+  dev_trace_end(p, range_end - range_begin, 8192 + blockIdx.x);
+#endif
+}
+
 // Combine the chunks of a split unit: out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being the
 // chunk's softmax reference in log2 units (-inf: the chunk saw no key of the row).
 // One workgroup per (unit, kv-head, 32-wide slice of d), same thread -> (row, d) mapping as the main kernel.
@@ -896,16 +1314,22 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
   const int tok = m.t0 + (r - hh * BMT);
   const int cu_s = p.cu_new_lens[m.s];
   const int N = p.cu_new_lens[m.s + 1] - cu_s;
-  const float* base = p.partials + ((int64_t)m.pslot0 * Hkv + kvh) * kPartialFloats + tid;
-  const int64_t chunk_stride = (int64_t)Hkv * kPartialFloats;
+  // chunk ch of a unit: slot pslot0 + ch; of a short turn cut by the decode kernel (negative count): its first piece
+  // in pslot0, piece ch >= 1 in the even slot of the ch-th workgroup after the one that wrote pslot0
+  const int n_chunks = m.n_chunks < 0 ? -m.n_chunks : m.n_chunks;
+  const int first_wg = (m.pslot0 - p.dec_pslot_base) >> 1;
+  auto chunk = [&](int ch) {
+    const int slot = (m.n_chunks > 0 || ch == 0) ? m.pslot0 + ch : p.dec_pslot_base + 2 * (first_wg + ch);
+    return p.partials + ((int64_t)slot * Hkv + kvh) * kPartialFloats + tid;
+  };
   float M = -INFINITY;
-  for (int ch = 0; ch < m.n_chunks; ++ch) M = fmaxf(M, base[ch * chunk_stride + 64 * 256]);
+  for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, chunk(ch)[64 * 256]);
   float acc[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   float L = 0.f;
-  for (int ch = 0; ch < m.n_chunks; ++ch) {
-    const float* part = base + ch * chunk_stride;
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    const float* part = chunk(ch);
     const float mc = part[64 * 256];
     const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);  // references are in log2 units
     L += w * part[65 * 256];
@@ -936,7 +1360,8 @@ static int env_int(const char* name, int dflt) {
 
 struct MfmaPlan {
   int32_t bmt, target, target_slots, c_min, units_bound, items_bound, merges_bound, pslots_bound;
-  int64_t off_items, off_merges, off_partials, total_bytes;
+  int32_t dec_wgs, dec_pslot_base;  // decode kernel: workgroups per kv-head, first of their 2 * dec_wgs slots
+  int64_t off_items, off_dec_s, off_dec_off, off_merges, off_partials, total_bytes;
 };
 
 static inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -956,8 +1381,18 @@ static MfmaPlan make_plan(int32_t n_sessions, int32_t n_q_heads, int32_t n_kv_he
   pl.items_bound = pl.units_bound + per_head;
   pl.merges_bound = per_head;
   pl.pslots_bound = 2 * per_head;
+  // decode kernel (batches of short turns only): one equal share of the keys per workgroup, two partial-result slots
+  // and at most one entry of the merge list per workgroup
+  pl.dec_wgs = env_int("SYMPH_ATTN_DECODE_WGS", 512) / n_kv_heads;
+  if (pl.dec_wgs < 1) pl.dec_wgs = 1;
+  pl.dec_pslot_base = pl.pslots_bound;
+  pl.pslots_bound += 2 * pl.dec_wgs;
+  pl.merges_bound += pl.dec_wgs;
+  const int32_t ns = n_sessions < kSchedMaxSessions ? n_sessions : kSchedMaxSessions;  // per scheduler slice
   pl.off_items = align256(kHdrInts * 4);
-  pl.off_merges = align256(pl.off_items + (int64_t)pl.items_bound * sizeof(WorkItem));
+  pl.off_dec_s = align256(pl.off_items + (int64_t)pl.items_bound * sizeof(WorkItem));
+  pl.off_dec_off = align256(pl.off_dec_s + (int64_t)ns * 4);
+  pl.off_merges = align256(pl.off_dec_off + (int64_t)(ns + 1) * 4);
   pl.off_partials = align256(pl.off_merges + (int64_t)pl.merges_bound * sizeof(MergeItem));
   pl.total_bytes = pl.off_partials + (int64_t)pl.pslots_bound * n_kv_heads * kPartialFloats * 4;
 #if SYMPH_DEV_TIMERS
@@ -1025,9 +1460,16 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   sp.coarse_ok = env_int("SYMPH_ATTN_COARSE", 1);
   sp.c_min = pl.c_min;
   sp.items_bound = pl.items_bound;
-  sp.merges_bound = pl.merges_bound;
-  sp.pslots_bound = pl.pslots_bound;
+  sp.merges_bound = pl.merges_bound - pl.dec_wgs;  // the work items' share; the rest is the decode kernel's
+  sp.pslots_bound = pl.dec_pslot_base;
   sp.hdr = (int32_t*)ws;
+  // A batch in which no session has more new rows than one wave holds (decode steps) takes the decode kernel.  Mixed
+  // batches do not: their short turns are memory-bound pieces that share the CUs with the compute-bound ones inside
+  // the main kernel, which measured faster than two kernels one after the other.
+  const bool dec_mode = env_int("SYMPH_ATTN_DECODE", 1) != 0 && a.max_new_len >= 1 && a.max_new_len * G <= 32;
+  sp.bmt_dec = dec_mode ? 32 / G : 0;
+  sp.dec_s = (int32_t*)(ws + pl.off_dec_s);
+  sp.dec_off = (int32_t*)(ws + pl.off_dec_off);
   sp.items = (WorkItem*)(ws + pl.off_items);
   sp.merges = (MergeItem*)(ws + pl.off_merges);
 
@@ -1053,6 +1495,10 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.hdr = sp.hdr;
   p.items = sp.items;
+  p.dec_s = sp.dec_s;
+  p.dec_off = sp.dec_off;
+  p.dec_pslot_base = pl.dec_pslot_base;
+  p.merges_bound = pl.merges_bound;
   p.merges = sp.merges;
   p.partials = (float*)(ws + pl.off_partials);
 #if SYMPH_DEV_TIMERS
@@ -1061,9 +1507,10 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
 
   const int64_t g_main = (int64_t)pl.items_bound * a.n_kv_heads;
   const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads * 4;
-  if (g_main > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
+  const int64_t g_dec = dec_mode ? (int64_t)pl.dec_wgs * a.n_kv_heads : 0;
+  if (g_main > 0x7FFFFFFFLL || g_dec > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
 #if SYMPH_DEV_TIMERS
-  if (g_main * 64 > (1 << 20)) return SYMPH_EUNSUPPORTED;
+  if (g_main > 8192 || (8192 + g_dec) * 64 > (1 << 20) - 512) return SYMPH_EUNSUPPORTED;
 #endif
   // The scheduler keeps one table entry per session in LDS: larger batches run as consecutive slices of sessions
   // (same stream, same workspace; the bounds of the whole batch cover every slice).
@@ -1081,6 +1528,12 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
     else
       hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+    if (g_dec > 0) {
+      if (a.block_size == 16)
+        hipLaunchKernelGGL((attn_decode_kernel<G, 4>), dim3((unsigned)g_dec), dim3(256), 0, stream, p);
+      else
+        hipLaunchKernelGGL((attn_decode_kernel<G, 0>), dim3((unsigned)g_dec), dim3(256), 0, stream, p);
+    }
     hipLaunchKernelGGL((attn_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;

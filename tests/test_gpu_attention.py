@@ -83,6 +83,42 @@ def test_attention_edge_cases(oracle_mod, kw):
     check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 31))
 
 
+@pytest.mark.parametrize("kw,n_wgs", [
+    # batches of short turns only (new rows x group size <= 32) take the decode kernel, which cuts the concatenated
+    # key ranges of all sessions into equal shares: many sessions per share, one session over many shares, both
+    (dict(prefix_dist=("uniform", 0, 90), new_dist=("const", 1), n_sessions=64, n_blocks=1024), 16),
+    (dict(prefix_dist=("uniform", 2000, 3000), new_dist=("const", 1), n_sessions=2, n_blocks=512), 512),
+    (dict(prefix_dist=("uniform", 1, 1500), new_dist=("uniform", 1, 8), n_sessions=9, n_blocks=1024), 64),
+    (dict(prefix_dist=("uniform", 1, 1500), new_dist=("uniform", 1, 8), n_sessions=9, n_blocks=1024), 8),
+    (dict(prefix_dist=("const", 31), new_dist=("const", 1), n_sessions=7), 64),       # one 32-key tile per session
+    (dict(prefix_dist=("const", 32), new_dist=("const", 1), n_sessions=7), 64),       # one key into the second tile
+    (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 32), n_q_heads=2, n_kv_heads=2, n_sessions=6), 32),
+    (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 4), n_q_heads=16, n_kv_heads=2, n_sessions=6), 32),
+    (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 2), n_q_heads=32, n_kv_heads=2, n_sessions=6), 32),
+    (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 0, 3), block_size=32, n_blocks=256, n_sessions=10), 32),
+    (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 3), block_size=64, n_blocks=128, n_sessions=10), 512),
+])
+def test_decode_batches(oracle_mod, monkeypatch, kw, n_wgs):
+    monkeypatch.setenv("SYMPH_ATTN_DECODE_WGS", str(n_wgs))
+    cfg = _cfg(**kw)
+    sess = W.make_sessions(cfg, 37)
+    check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 37), label=f"decode batch, {n_wgs} shares")
+
+
+def test_decode_batch_agrees_with_the_work_item_path(oracle_mod, monkeypatch):
+    """The same decode-shaped batch through the decode kernel and (switched off) through the main kernel."""
+    cfg = _cfg(prefix_dist=("uniform", 1, 2500), new_dist=("uniform", 1, 4), n_sessions=12, n_blocks=2048)
+    sess = W.make_sessions(cfg, 41)
+    inputs = W.make_attn_inputs(cfg, sess, 41)
+    got_dec, ref = check(oracle_mod, cfg, sess, inputs, label="decode kernel")
+    monkeypatch.setenv("SYMPH_ATTN_DECODE", "0")
+    got_main = gpu_attention(cfg, sess, inputs, scale=cfg.scale)
+    max_abs, rel = attn_errors(got_main, ref)
+    assert max_abs <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1]
+    d, _ = attn_errors(got_dec, widen(got_main).astype(np.float64))
+    assert d <= 2e-2
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_peaked_attention_with_position_coded_values(oracle_mod, dtype):
     """Each query is a scaled copy of one key, so its softmax concentrates there; V encodes (session, position,
