@@ -562,7 +562,7 @@ def main():
                                 **spread["prefix_prefill_attn"]},
         "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
         "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
-        "mfma_reference": mfma_ref,
+        "mfma_reference": {**mfma_ref, "attn_pct_of_short_reference": 100 * attn_tflops / mfma_ref["short"]["TFLOPs"]},
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
