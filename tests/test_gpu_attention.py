@@ -234,3 +234,38 @@ def test_attention_full_size_sampled_rows(oracle_mod, name, n_tokens):
         n_tokens += len(always)
     rows = _sample_tokens(sess, n_tokens, rng, always)
     check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess), token_subset=rows, label="full, sampled rows")
+
+
+def test_decode_step_full_size_every_row(oracle_mod):
+    """The 96 one-token rows of the mixed-resume workload as a batch of their own (what bench.py --only decode times):
+    the decode kernel's even split at full size, every output row against the oracle."""
+    import torch
+    import paper_2412_16434_amd as S
+    from gpu_util import DEV, to_dev, to_host
+    cfg = W.get_config("mixed_resume")
+    sess = W.make_sessions(cfg)
+    k_pool, v_pool, q, k_new, v_new = W.make_attn_inputs(cfg, sess)
+    idx = np.nonzero(sess.new_lens == 1)[0]
+    rows = sess.cu_new_lens[:-1][idx]
+    n = len(idx)
+    q1, kn1, vn1 = (np.ascontiguousarray(a[rows]) for a in (q, k_new, v_new))
+    prefix = np.ascontiguousarray(sess.prefix_lens[idx])
+    table = np.ascontiguousarray(sess.block_table[idx])
+    cu = np.arange(n + 1, dtype=np.int32)
+    ref = oracle_mod.prefix_prefill_attn(k_pool, v_pool, q1, kn1, vn1, cu, prefix, table, cfg.scale)
+    cache = S.KVCache(to_dev(k_pool)[None], to_dev(v_pool)[None])
+    qd = to_dev(q1)
+    out = torch.full_like(qd, float("nan"))
+    max_prefix = int(prefix.max())
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, n, cfg.n_q_heads, n, 1, max_prefix)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    S.prefix_prefill_attn(cache, 0, qd, to_dev(kn1), to_dev(vn1), out, torch.from_numpy(cu).to(DEV),
+                          torch.from_numpy(prefix).to(DEV), torch.from_numpy(table).to(DEV), 1, max_prefix, cfg.scale,
+                          workspace=ws)
+    torch.cuda.synchronize()
+    got = to_host(out)
+    assert np.all(np.isfinite(widen(got)))
+    max_abs, rel = attn_errors(got, ref)
+    print(f"[attn parity] decode step, {n} sessions, {int(prefix.sum())} cached tokens: max_abs={max_abs:.3e} rel_l2={rel:.3e}",
+          flush=True)
+    assert max_abs <= TOL["bf16"][0] and rel <= TOL["bf16"][1]
