@@ -119,6 +119,36 @@ def test_decode_batch_agrees_with_the_work_item_path(oracle_mod, monkeypatch):
     assert d <= 2e-2
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_seeded_random_batches(oracle_mod, monkeypatch, seed):
+    """Five drawn batches per seed: kv-heads, group size, block size, session count, length ranges, and whether the
+    batch is a decode step, a mix of short and long turns, or prefill turns only."""
+    rng = np.random.default_rng(900 + seed)
+    for c in range(5):
+        hkv = int(rng.choice([1, 2, 3, 8]))
+        g = int(rng.choice([1, 2, 4, 8, 16]))
+        bs = int(rng.choice([16, 32, 64]))
+        n_sess = int(rng.integers(1, 40))
+        pmax = int(rng.choice([40, 300, 1500, 5000]))
+        kind = str(rng.choice(["decode", "mixed", "prefill"]))
+        if kind == "decode":
+            new_dist = ("uniform", 0 if rng.random() < 0.3 else 1, max(1, 32 // g))
+        elif kind == "mixed":
+            new_dist = ("uniform", 0, int(rng.choice([8, 70, 200])))
+        else:
+            new_dist = ("uniform", 1, int(rng.choice([33, 150, 400])))
+        cfg = _cfg(name=f"random{seed}_{c}", n_q_heads=hkv * g, n_kv_heads=hkv, block_size=bs, n_sessions=n_sess,
+                   n_blocks=n_sess * ((pmax + 500) // bs + 2) + 8,
+                   prefix_dist=("uniform", 0 if rng.random() < 0.3 else 1, pmax), new_dist=new_dist)
+        case_seed = int(rng.integers(1, 1 << 30))
+        sess = W.make_sessions(cfg, case_seed)
+        if sess.total_new_tokens == 0:
+            continue
+        monkeypatch.setenv("SYMPH_ATTN_DECODE_WGS", str(int(rng.choice([8, 64, 512]))))
+        check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, case_seed),
+              label=f"{kind} S={n_sess} Hkv={hkv} G={g} bs={bs} pmax={pmax}")
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_peaked_attention_with_position_coded_values(oracle_mod, dtype):
     """Each query is a scaled copy of one key, so its softmax concentrates there; V encodes (session, position,
