@@ -48,6 +48,9 @@ def _load():
         for fn in (lib.oracle_kv_pack_layers, lib.oracle_kv_unpack_layers):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp, i32, i32]
+        for fn in (lib.oracle_kv_pack_tail, lib.oracle_kv_unpack_tail):
+            fn.restype = C.c_int
+            fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, i32, vp]
         lib.oracle_kv_append.restype = C.c_int
         lib.oracle_kv_append.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32]
         lib.oracle_prefix_prefill_attn.restype = C.c_int
@@ -141,6 +144,48 @@ def kv_unpack(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_
                                   table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf))
     if rc != 0:
         raise RuntimeError("oracle_kv_unpack failed")
+
+
+def tail_offsets(prefix_lens: np.ndarray, tail_begin: np.ndarray) -> np.ndarray:
+    """Exclusive prefix sum (int64, S+1 entries) of the tail lengths prefix_lens - tail_begin."""
+    t = prefix_lens.astype(np.int64) - tail_begin.astype(np.int64)
+    return np.concatenate([[0], np.cumsum(t)]).astype(np.int64)
+
+
+def kv_pack_tail(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+                 tail_begin: np.ndarray) -> np.ndarray:
+    """Gather tokens ``tail_begin[s] .. prefix_lens[s]-1`` of every session, all layers (Sec. 3.3 write-back of what a
+    turn added).  Returns the buffer: layout of a migration buffer for sessions of the tail lengths."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    tail_begin = _check(tail_begin, np.int32, "tail_begin")
+    S = prefix_lens.shape[0]
+    offsets = tail_offsets(prefix_lens, tail_begin)
+    buf = np.zeros(int(offsets[S]) * 2 * L * hkv * d, dtype=k_pool.dtype)
+    rc = _load().oracle_kv_pack_tail(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, _ptr(table),
+                                     table.shape[1], _ptr(prefix_lens), _ptr(tail_begin), _ptr(offsets), S, _ptr(buf))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_pack_tail failed")
+    return buf
+
+
+def kv_unpack_tail(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+                   tail_begin: np.ndarray, buf: np.ndarray) -> None:
+    """Scatter a tail buffer (see ``kv_pack_tail``) into the pools, in place; nothing but the tails' slots changes."""
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    tail_begin = _check(tail_begin, np.int32, "tail_begin")
+    buf = _check(buf, k_pool.dtype, "buf")
+    S = prefix_lens.shape[0]
+    offsets = tail_offsets(prefix_lens, tail_begin)
+    if buf.size != int(offsets[S]) * 2 * L * hkv * d:
+        raise ValueError("buffer size does not match the tails")
+    rc = _load().oracle_kv_unpack_tail(_ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb, _ptr(table),
+                                       table.shape[1], _ptr(prefix_lens), _ptr(tail_begin), _ptr(offsets), S, _ptr(buf))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_unpack_tail failed")
 
 
 def kv_pack_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,

@@ -130,6 +130,54 @@ int oracle_kv_unpack_layers(void* k_base, void* v_base, int64_t layer_stride, in
                  elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, (void*)buf, layer_begin, layer_end);
 }
 
+/* Write-back of what a turn added (Sec. 3.3: the slower tiers are kept up to date with newly generated K,V, layer by
+ * layer): only tokens tail_begin[s] .. prefix_lens[s]-1 of each session move.  The buffer has the layout of a whole
+ * migration buffer for sessions of tail length T_s = prefix_lens[s] - tail_begin[s]: offsets[] counts tail tokens,
+ * and row (s, l, kv, i) holds token tail_begin[s] + i.  With tail_begin = 0 this is the whole gather / scatter. */
+static int kv_copy_tail(int to_buffer, void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride,
+                        int32_t n_layers, int32_t block_size, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                        const int32_t* table, int32_t table_stride, const int32_t* prefix_lens,
+                        const int32_t* tail_begin, const int64_t* offsets, int32_t n_sessions, void* buf) {
+  if (elem_bytes != 2 && elem_bytes != 4) return -1;
+  const int64_t row = (int64_t)n_kv_heads * head_dim;
+  for (int32_t s = 0; s < n_sessions; ++s)
+    if (tail_begin[s] < 0 || tail_begin[s] > prefix_lens[s]) return -1;
+  for (int32_t s = 0; s < n_sessions; ++s) {
+    const int64_t T = prefix_lens[s] - tail_begin[s];
+    for (int32_t l = 0; l < n_layers; ++l)
+      for (int32_t kv = 0; kv < 2; ++kv)
+        for (int64_t i = 0; i < T; ++i) {
+          const int64_t t = tail_begin[s] + i;
+          const int64_t b = table[(int64_t)s * table_stride + t / block_size];
+          const int64_t pool_elem = (int64_t)l * layer_stride + b * block_stride + (t % block_size) * row;
+          const int64_t buf_elem = (offsets[s] * 2 * n_layers + ((int64_t)2 * l + kv) * T + i) * row;
+          char* in_pool = (char*)(kv ? v_base : k_base) + pool_elem * elem_bytes;
+          char* in_buf = (char*)buf + buf_elem * elem_bytes;
+          if (to_buffer)
+            memcpy(in_buf, in_pool, (size_t)row * elem_bytes);
+          else
+            memcpy(in_pool, in_buf, (size_t)row * elem_bytes);
+        }
+  }
+  return 0;
+}
+
+int oracle_kv_pack_tail(const void* k_base, const void* v_base, int64_t layer_stride, int64_t block_stride,
+                        int32_t n_layers, int32_t block_size, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                        const int32_t* table, int32_t table_stride, const int32_t* prefix_lens,
+                        const int32_t* tail_begin, const int64_t* offsets, int32_t n_sessions, void* buf) {
+  return kv_copy_tail(1, (void*)k_base, (void*)v_base, layer_stride, block_stride, n_layers, block_size, n_kv_heads,
+                      head_dim, elem_bytes, table, table_stride, prefix_lens, tail_begin, offsets, n_sessions, buf);
+}
+
+int oracle_kv_unpack_tail(void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride, int32_t n_layers,
+                          int32_t block_size, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                          const int32_t* table, int32_t table_stride, const int32_t* prefix_lens,
+                          const int32_t* tail_begin, const int64_t* offsets, int32_t n_sessions, const void* buf) {
+  return kv_copy_tail(0, k_base, v_base, layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim,
+                      elem_bytes, table, table_stride, prefix_lens, tail_begin, offsets, n_sessions, (void*)buf);
+}
+
 /* Append: the new turn's K,V rows of one layer go into the paged cache behind the session's prefix, so that the next
  * turn (or decode step) finds them there (Sec. 2.1 "KV Cache": the keys and values of every processed token are kept;
  * Sec. 3.3: a finished request's new K,V blocks join the session's cache).  Token i of session s has position

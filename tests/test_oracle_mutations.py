@@ -24,6 +24,8 @@ MUTATIONS = {
     "new_keys_offset_wrong": ("*elem = (((int64_t)cu_s + (j - P)) * n_kv_heads + g) * head_dim;",
                               "*elem = (((int64_t)(j - P)) * n_kv_heads + g) * head_dim;"),
     "bf16_widen_shift": ("<< 16;\n    float f;", "<< 15;\n    float f;"),
+    "tail_starts_at_token_zero": ("const int64_t t = tail_begin[s] + i;", "const int64_t t = i;"),
+    "tail_plane_stride_is_the_whole_length": ("((int64_t)2 * l + kv) * T + i) * row", "((int64_t)2 * l + kv) * prefix_lens[s] + i) * row"),
 }
 
 

@@ -514,3 +514,99 @@ def test_token_subset_matches_full(oracle_mod):
     assert np.array_equal(part[rows], full[rows])
     others = np.setdiff1d(np.arange(sess.total_new_tokens), rows)
     assert np.all(np.isnan(part[others]))
+
+
+# --------------------------------------------------------------------------------------------------------
+# write-back of what a turn added: tokens tail_begin[s] .. P_s - 1 only (Sec. 3.3)
+# --------------------------------------------------------------------------------------------------------
+def _tail_begins(sess, rng):
+    """Per session: 0, P_s (nothing new), or something in between."""
+    P = sess.prefix_lens.astype(np.int64)
+    pick = rng.integers(0, 4, size=P.shape[0])
+    b = np.where(pick == 0, 0, np.where(pick == 1, P, rng.integers(0, P + 1)))
+    return b.astype(np.int32)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_pack_tail_tagged_pool_layout(oracle_mod, seed):
+    """Every element of a tail buffer decodes to the coordinates the layout rules give: session-major over the tail
+    lengths, layer-major, K then V, token tail_begin + i."""
+    cfg = small_cfg("fp32", n_layers=3, n_sessions=5, n_blocks=64, prefix_dist=("uniform", 0, 23))
+    sess = W.make_sessions(cfg, seed)
+    begins = _tail_begins(sess, np.random.default_rng(seed))
+    k_pool, v_pool = tagged_pools(cfg)
+    buf = oracle_mod.kv_pack_tail(k_pool, v_pool, sess.block_table, sess.prefix_lens, begins)
+    H, d, bs = cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+    assert buf.size == int((sess.prefix_lens - begins).sum()) * 2 * cfg.n_layers * H * d
+    kv, l, b, o, g, c = decode_tag(buf.view(np.uint32), cfg)
+    pos = 0
+    for s in range(sess.n_sessions):
+        for layer in range(cfg.n_layers):
+            for which in (0, 1):
+                for t in range(int(begins[s]), int(sess.prefix_lens[s])):
+                    sl = slice(pos, pos + H * d)
+                    assert np.all(kv[sl] == which) and np.all(l[sl] == layer)
+                    assert np.all(b[sl] == sess.block_table[s, t // bs]) and np.all(o[sl] == t % bs)
+                    assert np.array_equal(g[sl], np.repeat(np.arange(H), d))
+                    assert np.array_equal(c[sl], np.tile(np.arange(d), H))
+                    pos += H * d
+    assert pos == buf.size
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_tail_completes_an_earlier_whole_pack(oracle_mod, dtype):
+    """Plane by plane (session, layer, K|V): the rows packed when the session had tail_begin tokens, followed by the
+    tail's rows, are the rows of a whole pack at the present length; with tail_begin = 0 the tail IS the whole pack."""
+    cfg = small_cfg(dtype, n_layers=3, n_sessions=6, n_blocks=96, prefix_dist=("uniform", 0, 40))
+    sess = W.make_sessions(cfg, 31)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 31)
+    begins = _tail_begins(sess, np.random.default_rng(31))
+    L, row = cfg.n_layers, cfg.n_kv_heads * cfg.head_dim
+    P = sess.prefix_lens
+    whole = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, P, sess.buf_token_offsets)
+    old_off = np.concatenate([[0], np.cumsum(begins)]).astype(np.int64)
+    old = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, begins, old_off)      # the cache as it was at length begin
+    tail = oracle_mod.kv_pack_tail(k_pool, v_pool, sess.block_table, P, begins)
+    tail_off = oracle_mod.tail_offsets(P, begins)
+    for s in range(sess.n_sessions):
+        Ps, Bs = int(P[s]), int(begins[s])
+        for plane in range(2 * L):
+            w0 = (int(sess.buf_token_offsets[s]) * 2 * L + plane * Ps) * row
+            o0 = (int(old_off[s]) * 2 * L + plane * Bs) * row
+            t0 = (int(tail_off[s]) * 2 * L + plane * (Ps - Bs)) * row
+            joined = np.concatenate([old[o0:o0 + Bs * row], tail[t0:t0 + (Ps - Bs) * row]])
+            assert joined.tobytes() == whole[w0:w0 + Ps * row].tobytes()
+    zero = np.zeros_like(begins)
+    assert oracle_mod.kv_pack_tail(k_pool, v_pool, sess.block_table, P, zero).tobytes() == whole.tobytes()
+    assert oracle_mod.kv_pack_tail(k_pool, v_pool, sess.block_table, P, P.copy()).size == 0
+
+
+def test_unpack_tail_touches_the_tail_slots_only(oracle_mod):
+    """Scattering a tail changes exactly the slots of tokens tail_begin .. P-1; after a whole unpack at the earlier
+    length it completes the pools to those of a whole unpack at the present length."""
+    cfg = small_cfg("bf16", n_layers=2, n_sessions=5, n_blocks=96, prefix_dist=("uniform", 0, 40))
+    sess = W.make_sessions(cfg, 32)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 32)
+    begins = _tail_begins(sess, np.random.default_rng(32))
+    P, dst = sess.prefix_lens, sess.dst_block_table
+    whole = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, P, sess.buf_token_offsets)
+    tail = oracle_mod.kv_pack_tail(k_pool, v_pool, sess.block_table, P, begins)
+    ks, vs = np.full_like(k_pool, 0x7FC1), np.full_like(v_pool, 0x7FC1)
+    oracle_mod.kv_unpack_tail(ks, vs, dst, P, begins, tail)
+    bs = cfg.block_size
+    touched = np.zeros(k_pool.shape[1:3], dtype=bool)           # [block, slot]
+    for s in range(sess.n_sessions):
+        for t in range(int(begins[s]), int(P[s])):
+            touched[dst[s, t // bs], t % bs] = True
+            assert np.array_equal(ks[:, dst[s, t // bs], t % bs], k_pool[:, sess.block_table[s, t // bs], t % bs])
+            assert np.array_equal(vs[:, dst[s, t // bs], t % bs], v_pool[:, sess.block_table[s, t // bs], t % bs])
+    assert np.all(ks[:, ~touched] == 0x7FC1) and np.all(vs[:, ~touched] == 0x7FC1)
+    # earlier whole unpack + tail == present whole unpack
+    old_off = np.concatenate([[0], np.cumsum(begins)]).astype(np.int64)
+    old = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, begins, old_off)
+    k2, v2 = np.full_like(k_pool, 0x7FC1), np.full_like(v_pool, 0x7FC1)
+    oracle_mod.kv_unpack(k2, v2, dst, begins, old_off, old)
+    oracle_mod.kv_unpack_tail(k2, v2, dst, P, begins, tail)
+    k3, v3 = np.full_like(k_pool, 0x7FC1), np.full_like(v_pool, 0x7FC1)
+    oracle_mod.kv_unpack(k3, v3, dst, P, sess.buf_token_offsets, whole)
+    assert k2.tobytes() == k3.tobytes() and v2.tobytes() == v3.tobytes()
