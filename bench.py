@@ -492,6 +492,23 @@ def main():
     append_us = e0.elapsed_time(e1) / 20 * 1e3
     append_bytes = 2.0 * 2.0 * sess.total_new_tokens * cfg.n_kv_heads * cfg.head_dim * 2   # K and V, read + written
 
+    # ---- write-back of what the turn added (all layers): only the new tokens of every session move --------------------
+    grown_h = (sess.prefix_lens + sess.new_lens).astype(np.int32)
+    tail_off_h = np.concatenate([[0], np.cumsum(sess.new_lens.astype(np.int64))]).astype(np.int64)
+    grown, tail_off = torch.from_numpy(grown_h).to(dev), torch.from_numpy(tail_off_h).to(dev)
+    tail_total = int(tail_off_h[-1])
+    tail_payload = S.kv_buffer_bytes(cache, tail_total)
+    tail_buf = buf[: tail_payload // 2]
+    for _ in range(2):
+        S.kv_pack_tail(cache, app_table, grown, prefix_lens, tail_off, tail_total, tail_buf)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        S.kv_pack_tail(cache, app_table, grown, prefix_lens, tail_off, tail_total, tail_buf)
+    e1.record()
+    torch.cuda.synchronize()
+    tail_ms = e0.elapsed_time(e1) / 10
+
     # ---- MFMA-only reference kernel: what the matrix cores deliver here, for a launch as short as the attention
     # call (the shader clock is still ramping up) and sustained ------------------------------------------------------
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
@@ -562,6 +579,8 @@ def main():
                                 **spread["prefix_prefill_attn"]},
         "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
         "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
+        "kv_pack_tail_new_turn": {"ms": tail_ms, "GBps": 2.0 * tail_payload / tail_ms / 1e6, "payload_bytes": tail_payload,
+                                  "pct_hbm_peak": 100 * 2.0 * tail_payload / tail_ms / 1e6 / HBM_PEAK_GBS},
         "mfma_reference": {**mfma_ref, "attn_pct_of_short_reference": 100 * attn_tflops / mfma_ref["short"]["TFLOPs"]},
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,

@@ -114,6 +114,24 @@ int32_t symph_kv_unpack_layers(const symph_kv_cache* cache, int32_t layer_begin,
                                const void* d_buf, int64_t buf_bytes, void* stream);
 
 /*
+ * Write-back of what a turn added (Sec. 3.3: the slower memory tiers are kept up to date with newly generated K,V, so
+ * that the fast tier can be purged at any time): the gather / scatter for tokens d_tail_begin[s] .. d_prefix_lens[s]-1
+ * of every session only, all layers.  The buffer has the layout of a migration buffer for sessions of the tail lengths
+ * T_s = prefix_lens[s] - tail_begin[s]: d_tail_offsets[S+1] (device, int64) is the exclusive prefix sum of the T_s,
+ * total_tail_tokens its last entry (host copy), row (s, l, K|V, i) holds token tail_begin[s] + i, buf_bytes >=
+ * symph_kv_buffer_bytes(cache, total_tail_tokens).  Appending, per (session, layer, K|V), a tail's rows to the rows
+ * packed when the session had tail_begin[s] tokens gives the rows of a whole pack at the present length.  A session
+ * with tail_begin[s] outside [0, prefix_lens[s]] is skipped.  Everything else as for symph_kv_pack / symph_kv_unpack.
+ */
+int32_t symph_kv_pack_tail(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
+                           const int32_t* d_prefix_lens, const int32_t* d_tail_begin, const int64_t* d_tail_offsets,
+                           int32_t n_sessions, int64_t total_tail_tokens, void* d_buf, int64_t buf_bytes, void* stream);
+int32_t symph_kv_unpack_tail(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,
+                             const int32_t* d_prefix_lens, const int32_t* d_tail_begin, const int64_t* d_tail_offsets,
+                             int32_t n_sessions, int64_t total_tail_tokens, const void* d_buf, int64_t buf_bytes,
+                             void* stream);
+
+/*
  * Append: write the new turn's K,V rows of one layer into the paged cache behind each session's prefix, so that the
  * next turn or decode step finds them there (Sec. 2.1 "KV Cache": the keys and values of every processed token are
  * kept; Sec. 3.3: the K,V a request produced join its session's cache).  Token i of session s has position P_s + i:

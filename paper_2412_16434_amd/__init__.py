@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     kv_unpack,
     kv_pack_layers,
     kv_unpack_layers,
+    kv_pack_tail,
+    kv_unpack_tail,
     kv_append,
     prefix_prefill_attn,
     prefix_prefill_attn_workspace_bytes,

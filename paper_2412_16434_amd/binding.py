@@ -15,7 +15,7 @@ SYMPH_BF16, SYMPH_FP32 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
-    "symph_kv_append",
+    "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
     "symph_mfma_reference",
@@ -58,6 +58,9 @@ def load_library():
     for fn in (lib.symph_kv_pack_layers, lib.symph_kv_unpack_layers):
         fn.restype = i32
         fn.argtypes = [cp, i32, i32, vp, i32, vp, vp, i32, i64, vp, i64, vp]
+    for fn in (lib.symph_kv_pack_tail, lib.symph_kv_unpack_tail):
+        fn.restype = i32
+        fn.argtypes = [cp, vp, i32, vp, vp, vp, i32, i64, vp, i64, vp]
     for fn in (lib.symph_stage_layer_to_host, lib.symph_stage_layer_to_device):
         fn.restype = i32
         fn.argtypes = [vp, vp, cp, i32, vp, vp, i32, vp, vp, vp]
@@ -184,6 +187,26 @@ def kv_unpack_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block
         dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
         prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
         "symph_kv_unpack_layers")
+
+
+def kv_pack_tail(cache: KVCache, block_table, prefix_lens, tail_begin, tail_offsets, total_tail_tokens: int, buf,
+                 stream=None) -> None:
+    """Gather tokens ``tail_begin[s] .. prefix_lens[s]-1`` of every session (all layers) into ``buf``."""
+    st = cache.struct()
+    _check(load_library().symph_kv_pack_tail(
+        C.byref(st), _ptr(block_table), block_table.shape[1] if block_table.dim() == 2 else 0, _ptr(prefix_lens),
+        _ptr(tail_begin), _ptr(tail_offsets), prefix_lens.shape[0], int(total_tail_tokens), _ptr(buf),
+        buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_pack_tail")
+
+
+def kv_unpack_tail(cache: KVCache, dst_block_table, prefix_lens, tail_begin, tail_offsets, total_tail_tokens: int, buf,
+                   stream=None) -> None:
+    """Scatter a tail buffer (see ``kv_pack_tail``) into the cache through ``dst_block_table``."""
+    st = cache.struct()
+    _check(load_library().symph_kv_unpack_tail(
+        C.byref(st), _ptr(dst_block_table), dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0,
+        _ptr(prefix_lens), _ptr(tail_begin), _ptr(tail_offsets), prefix_lens.shape[0], int(total_tail_tokens), _ptr(buf),
+        buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_unpack_tail")
 
 
 def kv_append(cache: KVCache, layer: int, k_new, v_new, cu_new_lens, prefix_lens, block_table, stream=None) -> None:

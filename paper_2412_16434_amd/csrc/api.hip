@@ -18,7 +18,7 @@ int32_t validate_cache(const symph_kv_cache* c) {
 static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
                        const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
                        const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
-                       int64_t buf_bytes, void* stream) {
+                       int64_t buf_bytes, void* stream, const int32_t* d_tail_begin = nullptr) {
   int32_t rc = validate_cache(cache);
   if (rc != SYMPH_OK) return rc;
   if (n_sessions < 0 || total_tokens < 0 || table_stride < 0 || buf_bytes < 0) return SYMPH_EINVAL;
@@ -28,8 +28,8 @@ static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_beg
   const int64_t need = symph_kv_buffer_bytes(cache, total_tokens);
   if (need < 0) return SYMPH_EINVAL;
   if (buf_bytes < need) return SYMPH_EWORKSPACE;
-  return launch_kv_migrate(pack, cache, layer_begin, layer_end, d_table, table_stride, d_prefix_lens, d_offsets,
-                           n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream);
+  return launch_kv_migrate(pack, cache, layer_begin, layer_end, d_table, table_stride, d_prefix_lens, d_tail_begin,
+                           d_offsets, n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream);
 }
 
 // The chunk of one layer of one session in the migration buffer (bytes): 2 * P rows of K then V.
@@ -96,6 +96,25 @@ int32_t symph_kv_pack_layers(const symph_kv_cache* cache, int32_t layer_begin, i
                              int64_t buf_bytes, void* stream) {
   return migrate(true, cache, layer_begin, layer_end, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets,
                  n_sessions, total_tokens, d_buf, buf_bytes, stream);
+}
+
+int32_t symph_kv_pack_tail(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
+                           const int32_t* d_prefix_lens, const int32_t* d_tail_begin, const int64_t* d_tail_offsets,
+                           int32_t n_sessions, int64_t total_tail_tokens, void* d_buf, int64_t buf_bytes, void* stream) {
+  if (!cache) return SYMPH_EINVAL;
+  if (n_sessions > 0 && total_tail_tokens > 0 && !d_tail_begin) return SYMPH_EINVAL;
+  return migrate(true, cache, 0, cache->n_layers, d_block_table, table_stride, d_prefix_lens, d_tail_offsets,
+                 n_sessions, total_tail_tokens, d_buf, buf_bytes, stream, d_tail_begin);
+}
+
+int32_t symph_kv_unpack_tail(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,
+                             const int32_t* d_prefix_lens, const int32_t* d_tail_begin, const int64_t* d_tail_offsets,
+                             int32_t n_sessions, int64_t total_tail_tokens, const void* d_buf, int64_t buf_bytes,
+                             void* stream) {
+  if (!cache) return SYMPH_EINVAL;
+  if (n_sessions > 0 && total_tail_tokens > 0 && !d_tail_begin) return SYMPH_EINVAL;
+  return migrate(false, cache, 0, cache->n_layers, d_dst_block_table, table_stride, d_prefix_lens, d_tail_offsets,
+                 n_sessions, total_tail_tokens, const_cast<void*>(d_buf), buf_bytes, stream, d_tail_begin);
 }
 
 int32_t symph_kv_unpack(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,

@@ -32,6 +32,8 @@ struct MigrateParams {
   const int32_t* table;
   int32_t table_stride;
   const int32_t* prefix_lens;
+  const int32_t* tail_begin;  // null: whole sessions; else only tokens tail_begin[s] .. prefix_lens[s]-1 move, and
+                              // offsets / total_tokens count those
   const int64_t* offsets;
   int32_t n_sessions;
   int64_t total_tokens;
@@ -89,10 +91,11 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   }
   const int32_t s = lo;
   const int64_t off_s = p.offsets[s];
-  const int32_t P = p.prefix_lens[s];
+  const int32_t first = p.tail_begin ? p.tail_begin[s] : 0;
+  const int32_t P = p.prefix_lens[s] - first;  // tokens of this session in the buffer
   const int64_t t64 = tg - off_s;
-  if (t64 >= P) return;  // inconsistent offsets / lengths: touch nothing
-  const int32_t t = (int32_t)t64;
+  if (first < 0 || t64 >= P) return;  // inconsistent offsets / lengths: touch nothing
+  const int32_t t = first + (int32_t)t64;  // position in the session
   const int32_t j = p.bs_shift >= 0 ? (t >> p.bs_shift) : t / p.block_size;
   if (j >= p.table_stride) return;
   const int32_t b = p.table[(int64_t)s * p.table_stride + j];
@@ -103,7 +106,7 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   if (sess_b + plane_b * p.n_planes > p.buf_bytes) return;  // the session would not fit the buffer: touch nothing
 
   const int64_t pool_off = (int64_t)b * p.block_stride_b + (int64_t)slot * p.row_bytes + (int64_t)col * sizeof(VecT);
-  const int64_t buf_off0 = sess_b + (int64_t)t * p.row_bytes + (int64_t)col * sizeof(VecT);
+  const int64_t buf_off0 = sess_b + t64 * p.row_bytes + (int64_t)col * sizeof(VecT);
 
   const int32_t plane0 = p.plane_begin + blockIdx.y * PLANES;
   VecT v[PLANES];
@@ -175,8 +178,8 @@ static int log2_or_neg(int64_t x) { return (x > 0 && (x & (x - 1)) == 0) ? __bui
 
 int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begin, int32_t layer_end,
                           const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
-                          const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
-                          int64_t buf_bytes, hipStream_t stream) {
+                          const int32_t* d_tail_begin, const int64_t* d_offsets, int32_t n_sessions,
+                          int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream) {
   const int eb = elem_bytes_of(c->dtype);
   const int64_t row_bytes = (int64_t)c->n_kv_heads * c->head_dim * eb;
   if (row_bytes > 0x7FFFFFFF) return SYMPH_EUNSUPPORTED;
@@ -205,6 +208,7 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begi
   p.table = d_table;
   p.table_stride = table_stride;
   p.prefix_lens = d_prefix_lens;
+  p.tail_begin = d_tail_begin;
   p.offsets = d_offsets;
   p.n_sessions = n_sessions;
   p.total_tokens = total_tokens;

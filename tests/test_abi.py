@@ -85,6 +85,9 @@ def test_host_validation_rejects_without_launching():
     assert lib.symph_kv_append(C.byref(good), 0, None, None, None, None, None, 0, 0, 0, None) == 0
     assert lib.symph_device_copy(0x10, 0x20, 24, None) == EUNSUP
     assert lib.symph_device_copy(0x18, 0x20, 32, None) == EUNSUP
+    assert lib.symph_kv_pack_tail(C.byref(good), 0x10, 4, 0x10, None, 0x10, 1, 8, 0x10, 1 << 20, None) == EINVAL      # no tail_begin
+    assert lib.symph_kv_unpack_tail(C.byref(good), 0x10, 4, 0x10, 0x10, 0x10, 1, 8, 0x10, 16, None) == EWS        # buffer too small
+    assert lib.symph_kv_pack_tail(C.byref(good), None, 0, None, None, None, 0, 0, None, 0, None) == 0
     assert lib.symph_mfma_reference(0, None, 0x10, None) == EINVAL
     assert lib.symph_mfma_reference(8, None, None, None) == EINVAL
     assert S.status_string(0) == "ok" and "unsupported" in S.status_string(-2)
