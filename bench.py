@@ -358,6 +358,33 @@ def pipelined_resume(args, cfg, sess):
 
     copy_ms, attn_ms = timed(copy_only), timed(attn_only_all_layers)
     shot_ms, wise_ms = timed(one_shot), timed(layer_wise)
+
+    # ---- the other direction (Sec. 3.3: layer-wise asynchronous writes): K,V of the batch go to pinned host memory.
+    # Whole sessions in one shot (pack, then one copy) and layer by layer (pack of layer l+1 overlaps the copy of layer
+    # l); and only what the turn added (pack_tail of the new tokens, then one copy of that).
+    src_table = torch.from_numpy(sess.table_with_room_for_the_new_turn()).to(dev)
+    ev_pack = [torch.cuda.Event() for _ in range(L)]
+
+    def write_back_one_shot():
+        S.kv_pack(cache, src_table, prefix_lens, offsets, total, dbuf, stream=s_unpack)
+        S.stage_to_host(host, dbuf, payload, s_unpack, s_copy, ev)
+
+    def write_back_layer_wise():
+        for l in range(L):
+            S.kv_pack_layers(cache, l, l + 1, src_table, prefix_lens, offsets, total, dbuf, stream=s_unpack)
+            S.stage_layer_to_host(host, dbuf, cache, l, h_prefix, h_off, s_unpack, s_copy, ev_pack[l])
+
+    grown = torch.from_numpy((sess.prefix_lens + sess.new_lens).astype(np.int32)).to(dev)
+    tail_off_h = np.concatenate([[0], np.cumsum(sess.new_lens.astype(np.int64))]).astype(np.int64)
+    tail_off = torch.from_numpy(tail_off_h).to(dev)
+    tail_total = int(tail_off_h[-1])
+    tail_payload = S.kv_buffer_bytes(cache, tail_total)
+
+    def write_back_tail():
+        S.kv_pack_tail(cache, src_table, grown, prefix_lens, tail_off, tail_total, dbuf, stream=s_unpack)
+        S.stage_to_host(host, dbuf, tail_payload, s_unpack, s_copy, ev)
+
+    wb_shot_ms, wb_wise_ms, wb_tail_ms = timed(write_back_one_shot), timed(write_back_layer_wise), timed(write_back_tail)
     print(json.dumps({
         "metric": "resume from pinned host memory: host->device + unpack + attention of all layers", "value": wise_ms,
         "unit": "ms", "n_gpus": 1, "steps": max(args.steps // 4, 3), "warmup": 1, "ms_per_step": wise_ms,
@@ -367,7 +394,9 @@ def pipelined_resume(args, cfg, sess):
         "host_to_device_alone": {"ms": copy_ms, "GBps": payload / copy_ms / 1e6},
         "attention_all_layers_kv_in_place": {"ms": attn_ms},
         "one_shot": {"ms": shot_ms, "after_the_copy_ms": shot_ms - copy_ms},
-        "layer_wise": {"ms": wise_ms, "after_the_copy_ms": wise_ms - copy_ms}}))
+        "layer_wise": {"ms": wise_ms, "after_the_copy_ms": wise_ms - copy_ms},
+        "write_back": {"whole_sessions_one_shot_ms": wb_shot_ms, "whole_sessions_layer_wise_ms": wb_wise_ms,
+                       "new_tokens_only_ms": wb_tail_ms, "new_tokens_payload_bytes": tail_payload}}))
 
 
 def main():
