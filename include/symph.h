@@ -76,7 +76,9 @@ int64_t symph_kv_buffer_bytes(const symph_kv_cache* cache, int64_t total_tokens)
  *   d_block_table [n_sessions][table_stride] int32, d_prefix_lens [n_sessions] int32,
  *   d_buf_token_offsets [n_sessions+1] int64 (exclusive prefix sum of prefix lengths),
  *   total_tokens = host copy of d_buf_token_offsets[n_sessions] (sizes the grid without a device read-back),
- *   d_buf: device, buf_bytes >= symph_kv_buffer_bytes(cache, total_tokens), 16-byte aligned.
+ *   d_buf: device, buf_bytes >= symph_kv_buffer_bytes(cache, total_tokens), 16-byte aligned.  Any address the
+ *   device can reach will do: pinned host memory that the runtime maps for the device (hipHostMalloc) makes the
+ *   kernel write (pack) or read (unpack) it over the host link, without a staging copy in device memory.
  * Reads only slots of valid tokens (never the unused tail of a partially filled last block); a block id may
  * appear in several sessions.  n_sessions == 0 or total_tokens == 0 is SYMPH_OK with no launch.
  * Needs row bytes (n_kv_heads*head_dim*elem) to be a multiple of 4 and strides/pointers aligned to

@@ -189,6 +189,33 @@ def test_pack_on_side_stream_and_host_staging(oracle_mod):
     assert to_host(dcache.k_pool).tobytes() == ks.tobytes() and to_host(dcache.v_pool).tobytes() == vs.tobytes()
 
 
+def test_buffer_in_mapped_pinned_host_memory(oracle_mod):
+    """The buffer argument may be pinned host memory that the runtime maps for the device at the same address: unpack
+    then reads it over PCIe, pack writes it, and no staging copy in HBM is needed."""
+    import ctypes
+    cfg = W.scaled_config(W.get_config("llama8b"), n_layers=3, n_sessions=5, prefix_scale=0.05, new_scale=0.2, n_blocks=512)
+    sess = W.make_sessions(cfg)
+    k_pool, v_pool = W.make_pool_host(cfg, sess)
+    ref_buf = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    host = torch.zeros(ref_buf.size, dtype=torch.int16, pin_memory=True)
+    mapped = ctypes.c_void_p(0)
+    rc = ctypes.CDLL("libamdhip64.so").hipHostGetDevicePointer(ctypes.byref(mapped), ctypes.c_void_p(host.data_ptr()), 0)
+    if rc != 0 or mapped.value != host.data_ptr():
+        pytest.skip("pinned host memory is not mapped for the device at its host address here")
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    hbuf = host.view(torch.bfloat16)
+    S.kv_pack(cache, ds.table, ds.prefix_lens, ds.offsets, sess.total_prefix_tokens, hbuf)
+    torch.cuda.synchronize()
+    assert host.numpy().view(np.uint16).tobytes() == ref_buf.tobytes()
+    ks, vs = sentinel_like(k_pool), sentinel_like(v_pool)
+    oracle_mod.kv_unpack(ks, vs, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, ref_buf)
+    dcache = S.KVCache(to_dev(sentinel_like(k_pool)), to_dev(sentinel_like(v_pool)))
+    S.kv_unpack(dcache, ds.dst_table, ds.prefix_lens, ds.offsets, sess.total_prefix_tokens, hbuf)
+    torch.cuda.synchronize()
+    assert to_host(dcache.k_pool).tobytes() == ks.tobytes() and to_host(dcache.v_pool).tobytes() == vs.tobytes()
+
+
 def test_device_copy_matches_source():
     src = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 22,), dtype=torch.int32, device=DEV)
     for n_bytes in (16, 4096, (1 << 24) - 16, 1 << 24):
