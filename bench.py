@@ -49,6 +49,17 @@ def parse_args():
     return ap.parse_args()
 
 
+def _cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, sess, budget_s: float):
     """Time the oracle, as it stands, on a bounded sample of the same workload on the host cores."""
     import oracle
@@ -95,7 +106,7 @@ def cpu_baseline(cfg, sess, budget_s: float):
     step_s = full_mig / (pack_gbs * 1e9) + full_mig / (unpack_gbs * 1e9) + sess.attn_flops() / (attn_gflops * 1e9)
     step_bytes = 2.0 * full_mig + sess.attn_bytes()
     return {
-        "value": step_bytes / step_s / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "value": step_bytes / step_s / 1e9, "unit": "GB/s", "cores": threads, "cpu_model": _cpu_model(), "kind": "oracle",
         "sample": (f"pack+unpack of {msess.n_sessions} sessions x {mcfg.n_layers} layers "
                    f"({msess.payload_bytes() / 1e6:.0f} MB payload, same shapes and length recipe); attention on "
                    f"{n_rows} of {T} query tokens of the real batch (all heads); step extrapolated from the three rates"),
