@@ -581,17 +581,34 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   };
   // Issue the loads of one tile of K or of V into an LDS buffer.  Rows that do not exist (past the session's keys, or
   // named by a block id outside the cache) are read from the page of zeros, so they are finite and add nothing.
+#if SYMPH_DEV_TIMERS
+  long long dev_dma = 0;  // clocks inside the fast path's four loads
+#endif
   auto issue_tile = [&](const char* pool_bytes, const __bf16* new_rows, char* lds_buf, int tile) {
     // one comparison of the largest id (as unsigned: a negative id is huge)
     const unsigned id_max = max(max((unsigned)ids[0], (unsigned)ids[1]), max((unsigned)ids[2], (unsigned)ids[3]));
     const bool fast = tile < fast_end && id_max < (unsigned)p.n_blocks;
-    if (fast) {
+    if (__builtin_expect(fast, 1)) {
+#if SYMPH_DEV_TIMERS
+      asm volatile("" ::: "memory");
+      const long long dma0 = clock64();
+#endif
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         uint64_t off = (uint64_t)(unsigned)ids[i] * p.block_bytes;
         if (LB != 4) off += (uint64_t)((tile * kBN + 16 * i) & bs_mask) * row_bytes;
-        SYMPH_GLDS16(pool_bytes + off + voff, lds_buf + (4 * i + wave) * kGroupBytes);
+        // Scalar base + 32-bit lane offset, kept apart for the compiler: with 64-bit per-lane addresses the issue of
+        // such a load waits for the matrix instructions of the SIMD's other wave (microbenchmark: eight loads take
+        // 290 clocks in this form whatever the other wave does, and 500-2100 in the other while it runs MFMAs).
+        const char* base = pool_bytes + off;
+        unsigned lane_off = voff;
+        asm("" : "+s"(base), "+v"(lane_off));
+        SYMPH_GLDS16(base + lane_off, lds_buf + (4 * i + wave) * kGroupBytes);
       }
+      asm volatile("; end of the scalar-base loads");  // keeps the last one from being merged with the other path's
+#if SYMPH_DEV_TIMERS
+      dev_dma += clock64() - dma0;
+#endif
     } else {
       // rare path: its per-lane address pieces are derived here, from a lane id the optimiser cannot see through, so
       // that they do not occupy registers throughout the main loop
@@ -790,17 +807,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #if SYMPH_DEV_TIMERS
     const long long ph0 = clock64();
 #endif
-    {
-      if (j + 1 < tile_end) {
-        int keep[4];
+    if (j + 1 < tile_end) {
+      int keep[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { keep[i] = ids[i]; ids[i] = ids_v[i]; }
-        issue_tile(v_bytes, p.v_new, v_other, j + 1);   // ids of tile j+1
+      for (int i = 0; i < 4; ++i) { keep[i] = ids[i]; ids[i] = ids_v[i]; }
+      issue_tile(v_bytes, p.v_new, v_other, j + 1);   // ids of tile j+1
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ids[i] = keep[i];
-      }
-      if (j + 2 < tile_end) issue_tile(k_bytes, p.k_new, k_same, j + 2);
+      for (int i = 0; i < 4; ++i) ids[i] = keep[i];
     }
+    if (j + 2 < tile_end) issue_tile(k_bytes, p.k_new, k_same, j + 2);
 #if SYMPH_DEV_TIMERS
     const long long ph1 = clock64();
 #endif
@@ -899,6 +914,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   if (blockIdx.x == 0 && (tid & 63) == 0) {  // per-phase shader clocks of each wave of workgroup 0
     long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16) + 8 * (tid >> 6);
     t[0] = dev_ph[0]; t[1] = dev_ph[1]; t[2] = dev_ph[2]; t[3] = dev_ph[3]; t[4] = clock64() - dev_c0; t[5] = tile_end - tile_begin;
+    t[6] = dev_dma;
   }
 #endif
   if (it.pslot < 0) {
@@ -1048,8 +1064,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
       for (int g = 0; g < 8; ++g) {
         uint64_t off = (uint64_t)(unsigned)(g < 4 ? ids.a : ids.b) * p.block_bytes + (uint64_t)(4 * (g & 3)) * row_bytes;
         if (LB != 4) off += (uint64_t)((u * kSub + 16 * (g >> 2)) & bs_mask) * row_bytes;
-        SYMPH_GLDS16_NT(pool + off + voff, buf + g * kGroupBytes);  // every cached row is read once per kv-head
+        const char* base = pool + off;  // scalar base + 32-bit lane offset, as in attn_mfma_kernel
+        unsigned lane_off = voff;
+        asm("" : "+s"(base), "+v"(lane_off));
+        SYMPH_GLDS16_NT(base + lane_off, buf + g * kGroupBytes);  // every cached row is read once per kv-head
       }
+      asm volatile("; end of the scalar-base loads");
     } else {
       const unsigned in_row = (unsigned)kvh * 256u + (unsigned)((lane & 15) ^ (((lane >> 4) & 3) << 2)) * 16u;
       const char* const zeros = reinterpret_cast<const char*>(p.hdr + kZeroPageInt) + (lane & 15) * 16;
