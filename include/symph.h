@@ -46,7 +46,8 @@ typedef enum {
   SYMPH_EINVAL = -1,       /* null pointer, non-positive shape, inconsistent sizes, bad scale */
   SYMPH_EUNSUPPORTED = -2, /* shape / dtype / alignment the kernels do not cover */
   SYMPH_ELAUNCH = -3,      /* the HIP runtime refused the launch or copy */
-  SYMPH_EWORKSPACE = -4    /* workspace or buffer smaller than required */
+  SYMPH_EWORKSPACE = -4,   /* workspace or buffer smaller than required */
+  SYMPH_ENOMEM = -5        /* host memory exhausted (only the stateful host objects of symph_pool.h allocate) */
 } symph_status;
 
 typedef enum { SYMPH_BF16 = 0, SYMPH_FP32 = 1 } symph_dtype;

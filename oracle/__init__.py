@@ -51,6 +51,9 @@ def _load():
         for fn in (lib.oracle_kv_pack_tail, lib.oracle_kv_unpack_tail):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, i32, vp]
+        for fn in (lib.oracle_kv_pack_units, lib.oracle_kv_unpack_units):
+            fn.restype = C.c_int
+            fn.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp]
         lib.oracle_kv_append.restype = C.c_int
         lib.oracle_kv_append.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32]
         lib.oracle_prefix_prefill_attn.restype = C.c_int
@@ -186,6 +189,46 @@ def kv_unpack_tail(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, pr
                                        table.shape[1], _ptr(prefix_lens), _ptr(tail_begin), _ptr(offsets), S, _ptr(buf))
     if rc != 0:
         raise RuntimeError("oracle_kv_unpack_tail failed")
+
+
+def unit_chunk_rows(offsets: np.ndarray, prefix_lens: np.ndarray, n_layers: int, s: int, layer: int) -> int:
+    """Row of a whole migration buffer at which the K rows of layer ``layer`` of session ``s`` begin."""
+    return int(offsets[s]) * 2 * n_layers + 2 * layer * int(prefix_lens[s])
+
+
+def _units_args(k_slots, v_slots, table, unit_lens, chunk_rows, buf):
+    L, n_slots, bs, hkv, d, eb, _, bst = _pool_geometry(k_slots, v_slots)
+    if L != 1:
+        raise ValueError("the slot pool is [n_slots][bs][H_kv][d]")
+    table = _check(table, np.int32, "table")
+    unit_lens = _check(unit_lens, np.int32, "unit_lens")
+    chunk_rows = _check(chunk_rows, np.int64, "chunk_rows")
+    buf = _check(buf, k_slots.dtype, "buf")
+    U = unit_lens.shape[0]
+    row = hkv * d
+    for u in range(U):      # the oracle checks its inputs on the host: every row inside the buffer, every slot in the pool
+        if chunk_rows[u] < 0 or (int(chunk_rows[u]) + 2 * int(unit_lens[u])) * row > buf.size:
+            raise ValueError("a unit lies outside the buffer")
+        nb = -(-int(unit_lens[u]) // bs)
+        if nb > table.shape[1] or (nb and (table[u, :nb].min() < 0 or table[u, :nb].max() >= n_slots)):
+            raise ValueError("a unit's table names a slot outside the pool")
+    return (_ptr(k_slots), _ptr(v_slots), bst, bs, hkv, d, eb, _ptr(table), table.shape[1], _ptr(unit_lens),
+            _ptr(chunk_rows), U, _ptr(buf))
+
+
+def kv_pack_units(k_slots: np.ndarray, v_slots: np.ndarray, table: np.ndarray, unit_lens: np.ndarray,
+                  chunk_rows: np.ndarray, buf: np.ndarray) -> None:
+    """Gather single layers of sessions ("units", Sec. 3.3 priority-based K,V cache) from one pool of slots
+    ``[n_slots][bs][H_kv][d]`` into their chunks of ``buf`` (modified in place; nothing else in it changes)."""
+    if _load().oracle_kv_pack_units(*_units_args(k_slots, v_slots, table, unit_lens, chunk_rows, buf)) != 0:
+        raise RuntimeError("oracle_kv_pack_units failed")
+
+
+def kv_unpack_units(k_slots: np.ndarray, v_slots: np.ndarray, table: np.ndarray, unit_lens: np.ndarray,
+                    chunk_rows: np.ndarray, buf: np.ndarray) -> None:
+    """Scatter the units' chunks of ``buf`` into their slots (pool modified in place; nothing else in it changes)."""
+    if _load().oracle_kv_unpack_units(*_units_args(k_slots, v_slots, table, unit_lens, chunk_rows, buf)) != 0:
+        raise RuntimeError("oracle_kv_unpack_units failed")
 
 
 def kv_pack_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,

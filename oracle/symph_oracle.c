@@ -178,6 +178,49 @@ int oracle_kv_unpack_tail(void* k_base, void* v_base, int64_t layer_stride, int6
                       elem_bytes, table, table_stride, prefix_lens, tail_begin, offsets, n_sessions, (void*)buf);
 }
 
+/* Unit-wise copy (Sec. 3.3, priority-based K,V cache: single layers of sessions are moved in and given up, lower
+ * layers first, and with several announced sessions only their lower layers may be resident).  The cache memory is
+ * ONE pool of slots, each a block of any layer; unit u is one layer of one session: unit_lens[u] tokens, token t in
+ * slot table[u][t / block_size] at position t % block_size, and in the buffer its K rows start at row chunk_rows[u],
+ * its V rows unit_lens[u] rows later (where layer l of session s lies in a whole migration buffer:
+ * chunk_rows = offsets[s] * 2 * n_layers + 2 * l * P_s).  Nothing else in the pool or the buffer changes. */
+static int kv_copy_units(int to_buffer, void* k_base, void* v_base, int64_t block_stride, int32_t block_size,
+                         int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes, const int32_t* table,
+                         int32_t table_stride, const int32_t* unit_lens, const int64_t* chunk_rows, int32_t n_units,
+                         void* buf) {
+  if (elem_bytes != 2 && elem_bytes != 4) return -1;
+  const int64_t row = (int64_t)n_kv_heads * head_dim;
+  for (int32_t u = 0; u < n_units; ++u)
+    for (int32_t kv = 0; kv < 2; ++kv)
+      for (int64_t t = 0; t < unit_lens[u]; ++t) {
+        const int64_t slot = table[(int64_t)u * table_stride + t / block_size];
+        const int64_t pool_elem = slot * block_stride + (t % block_size) * row;
+        const int64_t buf_elem = (chunk_rows[u] + (int64_t)kv * unit_lens[u] + t) * row;
+        char* in_pool = (char*)(kv ? v_base : k_base) + pool_elem * elem_bytes;
+        char* in_buf = (char*)buf + buf_elem * elem_bytes;
+        if (to_buffer)
+          memcpy(in_buf, in_pool, (size_t)row * elem_bytes);
+        else
+          memcpy(in_pool, in_buf, (size_t)row * elem_bytes);
+      }
+  return 0;
+}
+
+int oracle_kv_pack_units(const void* k_base, const void* v_base, int64_t block_stride, int32_t block_size,
+                         int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes, const int32_t* table,
+                         int32_t table_stride, const int32_t* unit_lens, const int64_t* chunk_rows, int32_t n_units,
+                         void* buf) {
+  return kv_copy_units(1, (void*)k_base, (void*)v_base, block_stride, block_size, n_kv_heads, head_dim, elem_bytes,
+                       table, table_stride, unit_lens, chunk_rows, n_units, buf);
+}
+
+int oracle_kv_unpack_units(void* k_base, void* v_base, int64_t block_stride, int32_t block_size, int32_t n_kv_heads,
+                           int32_t head_dim, int32_t elem_bytes, const int32_t* table, int32_t table_stride,
+                           const int32_t* unit_lens, const int64_t* chunk_rows, int32_t n_units, const void* buf) {
+  return kv_copy_units(0, k_base, v_base, block_stride, block_size, n_kv_heads, head_dim, elem_bytes, table,
+                       table_stride, unit_lens, chunk_rows, n_units, (void*)buf);
+}
+
 /* Append: the new turn's K,V rows of one layer go into the paged cache behind the session's prefix, so that the next
  * turn (or decode step) finds them there (Sec. 2.1 "KV Cache": the keys and values of every processed token are kept;
  * Sec. 3.3: a finished request's new K,V blocks join the session's cache).  Token i of session s has position

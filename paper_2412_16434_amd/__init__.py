@@ -6,6 +6,7 @@ is loaded on first use and a missing library is an error, never a fallback.
 """
 from .binding import (  # noqa: F401
     KVCache,
+    KvPool,
     SymphError,
     lib_path,
     load_library,

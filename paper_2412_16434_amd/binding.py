@@ -20,6 +20,10 @@ EXPORTED_SYMBOLS = (
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
     "symph_mfma_reference",
     "symph_status_string",
+    # symph_pool.h (host code only)
+    "symph_pool_create", "symph_pool_destroy", "symph_pool_advise", "symph_pool_drop", "symph_pool_claim",
+    "symph_pool_framework_take", "symph_pool_framework_give", "symph_pool_settle", "symph_pool_resident_layers",
+    "symph_pool_table", "symph_pool_counts",
 )
 
 
@@ -33,6 +37,11 @@ class _CacheStruct(C.Structure):
     _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("layer_stride", C.c_int64),
                 ("block_stride", C.c_int64), ("n_layers", C.c_int32), ("n_blocks", C.c_int32),
                 ("block_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+
+
+class _PoolChange(C.Structure):
+    _fields_ = [("session", C.c_int64), ("layer", C.c_int32), ("kind", C.c_int32), ("n_slots", C.c_int32),
+                ("slot_begin", C.c_int32)]
 
 
 def lib_path() -> str:
@@ -80,6 +89,29 @@ def load_library():
     lib.symph_mfma_reference.argtypes = [i32, C.POINTER(C.c_int64), vp, vp]
     lib.symph_status_string.restype = C.c_char_p
     lib.symph_status_string.argtypes = [i32]
+    ip = C.POINTER(i32)
+    lib.symph_pool_create.restype = i32
+    lib.symph_pool_create.argtypes = [i32, i32, i32, C.POINTER(vp)]
+    lib.symph_pool_destroy.restype = None
+    lib.symph_pool_destroy.argtypes = [vp]
+    lib.symph_pool_advise.restype = i32
+    lib.symph_pool_advise.argtypes = [vp, i64, i32]
+    lib.symph_pool_drop.restype = i32
+    lib.symph_pool_drop.argtypes = [vp, i64]
+    lib.symph_pool_claim.restype = i32
+    lib.symph_pool_claim.argtypes = [vp, i64, ip, i32, ip]
+    lib.symph_pool_framework_take.restype = i32
+    lib.symph_pool_framework_take.argtypes = [vp, i32, ip]
+    lib.symph_pool_framework_give.restype = i32
+    lib.symph_pool_framework_give.argtypes = [vp, i32, ip]
+    lib.symph_pool_settle.restype = i32
+    lib.symph_pool_settle.argtypes = [vp, C.POINTER(_PoolChange), i32, ip, i32, ip, ip]
+    lib.symph_pool_resident_layers.restype = i32
+    lib.symph_pool_resident_layers.argtypes = [vp, i64]
+    lib.symph_pool_table.restype = i32
+    lib.symph_pool_table.argtypes = [vp, i64, i32, ip, i32]
+    lib.symph_pool_counts.restype = i32
+    lib.symph_pool_counts.argtypes = [vp, ip, ip, ip]
     _lib = lib
     return lib
 
@@ -281,3 +313,95 @@ def mfma_reference(iters: int, sink, stream=None) -> int:
 def device_copy(dst, src, nbytes: int, stream=None) -> None:
     _check(load_library().symph_device_copy(_ptr(dst), _ptr(src), int(nbytes), _stream_ptr(stream)),
            "symph_device_copy")
+
+
+class KvPool:
+    """The pool object of ``include/symph_pool.h`` (host code): which layers of which announced sessions hold slots lent
+    by the framework.  Every method is one C call plus marshalling; failures raise SymphError and change nothing."""
+
+    EVICTED, LOAD = 0, 1
+
+    def __init__(self, n_layers: int, n_slots: int, block_size: int):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        self.n_layers, self.n_slots, self.block_size = n_layers, n_slots, block_size
+        st = self._lib.symph_pool_create(n_layers, n_slots, block_size, C.byref(self._h))
+        if st != 0:
+            raise SymphError(st, "symph_pool_create")
+
+    def close(self):
+        if self._h:
+            self._lib.symph_pool_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int, where: str) -> int:
+        if st < 0:
+            raise SymphError(st, where)
+        return st
+
+    def advise(self, session: int, n_tokens: int) -> None:
+        self._check(self._lib.symph_pool_advise(self._h, session, n_tokens), "symph_pool_advise")
+
+    def drop(self, session: int) -> None:
+        self._check(self._lib.symph_pool_drop(self._h, session), "symph_pool_drop")
+
+    def resident_layers(self, session: int) -> int:
+        return self._check(self._lib.symph_pool_resident_layers(self._h, session), "symph_pool_resident_layers")
+
+    def counts(self) -> tuple[int, int, int]:
+        f, l, w = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(self._lib.symph_pool_counts(self._h, C.byref(f), C.byref(l), C.byref(w)), "symph_pool_counts")
+        return f.value, l.value, w.value
+
+    def table(self, session: int, layer: int) -> list[int]:
+        cap = self.n_slots
+        buf = (C.c_int32 * cap)()
+        n = self._check(self._lib.symph_pool_table(self._h, session, layer, buf, cap), "symph_pool_table")
+        return list(buf[:n])
+
+    def claim(self, session: int) -> list[list[int]]:
+        """Tables of the resident layers, which now belong to the framework."""
+        cap = self.n_slots
+        buf = (C.c_int32 * cap)()
+        r = C.c_int32()
+        lent_before = self.counts()[1]
+        self._check(self._lib.symph_pool_claim(self._h, session, buf, cap, C.byref(r)), "symph_pool_claim")
+        if r.value == 0:
+            return []
+        n = lent_before - self.counts()[1]          # r tables of equal length, back to back
+        b = n // r.value
+        return [list(buf[i * b:(i + 1) * b]) for i in range(r.value)]
+
+    def framework_take(self, n: int) -> list[int]:
+        buf = (C.c_int32 * max(n, 1))()
+        self._check(self._lib.symph_pool_framework_take(self._h, n, buf), "symph_pool_framework_take")
+        return list(buf[:n])
+
+    def framework_give(self, slots) -> None:
+        n = len(slots)
+        buf = (C.c_int32 * max(n, 1))(*slots)
+        self._check(self._lib.symph_pool_framework_give(self._h, n, buf), "symph_pool_framework_give")
+
+    def settle(self) -> list[tuple[int, int, int, list[int]]]:
+        """[(kind, session, layer, slots)] — evictions first (slots empty), then loads, the most important first."""
+        nc, ns = C.c_int32(), C.c_int32()
+        st = self._lib.symph_pool_settle(self._h, None, 0, None, 0, C.byref(nc), C.byref(ns))
+        if st == 0:
+            return []
+        if st != -4:
+            raise SymphError(st, "symph_pool_settle")
+        changes = (_PoolChange * max(nc.value, 1))()
+        slots = (C.c_int32 * max(ns.value, 1))()
+        self._check(self._lib.symph_pool_settle(self._h, changes, nc.value, slots, ns.value, C.byref(nc), C.byref(ns)),
+                    "symph_pool_settle")
+        out = []
+        for c in changes[:nc.value]:
+            own = list(slots[c.slot_begin:c.slot_begin + c.n_slots]) if c.kind == self.LOAD else []
+            out.append((c.kind, c.session, c.layer, own))
+        return out

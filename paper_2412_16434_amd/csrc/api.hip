@@ -266,6 +266,7 @@ const char* symph_status_string(int32_t status) {
     case SYMPH_EUNSUPPORTED: return "unsupported shape, dtype or alignment";
     case SYMPH_ELAUNCH: return "HIP launch or copy failed";
     case SYMPH_EWORKSPACE: return "buffer or workspace too small";
+    case SYMPH_ENOMEM: return "out of host memory";
     default: return "unknown status";
   }
 }

@@ -26,6 +26,9 @@ MUTATIONS = {
     "bf16_widen_shift": ("<< 16;\n    float f;", "<< 15;\n    float f;"),
     "tail_starts_at_token_zero": ("const int64_t t = tail_begin[s] + i;", "const int64_t t = i;"),
     "tail_plane_stride_is_the_whole_length": ("((int64_t)2 * l + kv) * T + i) * row", "((int64_t)2 * l + kv) * prefix_lens[s] + i) * row"),
+    "unit_v_rows_not_behind_the_k_rows": ("(chunk_rows[u] + (int64_t)kv * unit_lens[u] + t) * row", "(chunk_rows[u] + t) * row"),
+    "unit_chunk_of_the_first_unit": ("(chunk_rows[u] + (int64_t)kv * unit_lens[u] + t) * row", "(chunk_rows[0] + (int64_t)kv * unit_lens[u] + t) * row"),
+    "unit_slot_from_the_first_table_row": ("table[(int64_t)u * table_stride + t / block_size];", "table[t / block_size];"),
     # the residency oracle (priority.py)
     "admits_later_layers_first": ("keyed.append((layer, -blocks_of(n_tokens, block_size), sid))",
                                   "keyed.append((-layer, -blocks_of(n_tokens, block_size), sid))", "priority.py"),

@@ -610,3 +610,108 @@ def test_unpack_tail_touches_the_tail_slots_only(oracle_mod):
     k3, v3 = np.full_like(k_pool, 0x7FC1), np.full_like(v_pool, 0x7FC1)
     oracle_mod.kv_unpack(k3, v3, dst, P, sess.buf_token_offsets, whole)
     assert k2.tobytes() == k3.tobytes() and v2.tobytes() == v3.tobytes()
+
+
+# --------------------------------------------------------------------------------------------------------
+# unit-wise copies: single layers of sessions in one pool of slots (Sec. 3.3, priority-based K,V cache)
+# --------------------------------------------------------------------------------------------------------
+def random_units(rng, n_units, n_slots, bs, max_len, row, gap_rows=3):
+    """Units with disjoint random slot tables and chunks placed in random order with gaps in one buffer."""
+    lens = rng.integers(0, max_len + 1, size=n_units).astype(np.int32)
+    nbs = -(-lens // bs)
+    perm = rng.permutation(n_slots)[: int(nbs.sum())].astype(np.int32)
+    stride = max(int(nbs.max()), 1) + 1
+    table = np.full((n_units, stride), -7, dtype=np.int32)
+    at = 0
+    for u in range(n_units):
+        table[u, : nbs[u]] = perm[at: at + nbs[u]]
+        at += nbs[u]
+    chunk_rows = np.zeros(n_units, dtype=np.int64)
+    row_at = 2
+    for u in rng.permutation(n_units):
+        chunk_rows[u] = row_at
+        row_at += 2 * int(lens[u]) + int(rng.integers(0, gap_rows + 1))
+    return lens, table, chunk_rows, row_at + 1
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_pack_units_tagged_slot_pool(oracle_mod, seed):
+    rng = np.random.default_rng(400 + seed)
+    cfg = small_cfg("fp32", n_layers=1, n_blocks=60)
+    H, d, bs = cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+    k_slots, v_slots = tagged_pools(cfg)
+    lens, table, chunk_rows, n_rows = random_units(rng, 7, cfg.n_blocks, bs, 21, H * d)
+    sentinel = np.float32(-123.0)
+    buf = np.full(n_rows * H * d, sentinel, dtype=np.float32)
+    oracle_mod.kv_pack_units(k_slots[0], v_slots[0], table, lens, chunk_rows, buf)
+    kv, l, b, o, g, c = decode_tag(buf.view(np.uint32), cfg)
+    written = np.zeros(n_rows, dtype=bool)
+    for u in range(7):
+        for which in (0, 1):
+            for t in range(int(lens[u])):
+                r = int(chunk_rows[u]) + which * int(lens[u]) + t
+                sl = slice(r * H * d, (r + 1) * H * d)
+                assert np.all(kv[sl] == which) and np.all(b[sl] == table[u, t // bs]) and np.all(o[sl] == t % bs)
+                assert np.array_equal(g[sl], np.repeat(np.arange(H), d)) and np.array_equal(c[sl], np.tile(np.arange(d), H))
+                written[r] = True
+    untouched = buf.reshape(n_rows, H * d)[~written]
+    assert np.all(untouched == sentinel)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_unpack_units_round_trips_and_leaves_other_bytes_alone(oracle_mod, dtype):
+    rng = np.random.default_rng(77)
+    cfg = small_cfg(dtype, n_layers=1, n_blocks=50)
+    H, d, bs = cfg.n_kv_heads, cfg.head_dim, cfg.block_size
+    lens, table, chunk_rows, n_rows = random_units(rng, 6, cfg.n_blocks, bs, 18, H * d)
+    np_dtype = np.uint16 if dtype == "bf16" else np.float32
+    buf = rng.integers(1, 60000, size=n_rows * H * d).astype(np_dtype)
+    k_slots = np.full((cfg.n_blocks, bs, H, d), 7, dtype=np_dtype)
+    v_slots = np.full((cfg.n_blocks, bs, H, d), 9, dtype=np_dtype)
+    oracle_mod.kv_unpack_units(k_slots, v_slots, table, lens, chunk_rows, buf)
+    owned = np.zeros((cfg.n_blocks, bs), dtype=bool)
+    rows = buf.reshape(n_rows, H, d)
+    for u in range(6):
+        for t in range(int(lens[u])):
+            slot, o = table[u, t // bs], t % bs
+            owned[slot, o] = True
+            assert np.array_equal(k_slots[slot, o], rows[int(chunk_rows[u]) + t])
+            assert np.array_equal(v_slots[slot, o], rows[int(chunk_rows[u]) + int(lens[u]) + t])
+    assert np.all(k_slots[~owned] == 7) and np.all(v_slots[~owned] == 9)
+    back = np.zeros_like(buf)
+    oracle_mod.kv_pack_units(k_slots, v_slots, table, lens, chunk_rows, back)
+    mask = np.zeros(n_rows, dtype=bool)
+    for u in range(6):
+        mask[int(chunk_rows[u]): int(chunk_rows[u]) + 2 * int(lens[u])] = True
+    assert np.array_equal(back.reshape(n_rows, -1)[mask], buf.reshape(n_rows, -1)[mask])
+    assert np.all(back.reshape(n_rows, -1)[~mask] == 0)
+
+
+def test_units_of_the_lower_layers_equal_the_layer_range_scatter(oracle_mod):
+    """A cache of L layers seen as one pool of L * n_blocks slots (slot = layer * n_blocks + block): scattering the
+    units (s, l) for l < r_s is the layer-range scatter, session by session."""
+    cfg = small_cfg("bf16", n_layers=3, n_sessions=3, prefix_dist=("uniform", 1, 19))
+    sess = W.make_sessions(cfg, 5)
+    rng = np.random.default_rng(5)
+    L, nb, bs, H, d = cfg.n_layers, cfg.n_blocks, cfg.block_size, cfg.n_kv_heads, cfg.head_dim
+    total = int(sess.buf_token_offsets[-1])
+    buf = rng.integers(1, 60000, size=total * 2 * L * H * d).astype(np.uint16)
+    resident = [3, 1, 2]
+    # route 1: unit-wise into the flat pool
+    k_flat = np.zeros((L * nb, bs, H, d), dtype=np.uint16)
+    v_flat = np.zeros_like(k_flat)
+    units = [(s, l) for s in range(3) for l in range(resident[s])]
+    lens = np.array([sess.prefix_lens[s] for s, _ in units], dtype=np.int32)
+    table = np.stack([np.where(sess.block_table[s] >= 0, sess.block_table[s] + l * nb, 0) for s, l in units]).astype(np.int32)
+    chunk_rows = np.array([oracle_mod.unit_chunk_rows(sess.buf_token_offsets, sess.prefix_lens, L, s, l) for s, l in units],
+                          dtype=np.int64)
+    oracle_mod.kv_unpack_units(k_flat, v_flat, table, lens, chunk_rows, buf)
+    # route 2: the layer-range scatter of the L-layer cache, one session at a time
+    k_pool = np.zeros((L, nb, bs, H, d), dtype=np.uint16)
+    v_pool = np.zeros_like(k_pool)
+    for s in range(3):
+        lens_s = np.where(np.arange(3) == s, sess.prefix_lens, 0).astype(np.int32)   # other sessions: nothing to move
+        # offsets stay those of the whole buffer, so the chunks are found where they are
+        oracle_mod.kv_unpack_layers(k_pool, v_pool, sess.block_table, lens_s, sess.buf_token_offsets, buf, 0, resident[s])
+    assert np.array_equal(k_flat.reshape(L, nb, bs, H, d), k_pool) and np.array_equal(v_flat.reshape(L, nb, bs, H, d), v_pool)
+    assert k_pool.any()
