@@ -204,6 +204,27 @@ int32_t symph_stage_layer_to_device(void* d_buf, const void* h_pinned, const sym
                                     const int32_t* h_prefix_lens, const int64_t* h_buf_token_offsets,
                                     int32_t n_sessions, void* consumer_stream, void* side_stream, void* event);
 
+/*
+ * Unit-wise gather / scatter (Sec. 3.3, priority-based K,V cache: single layers of sessions are moved in, lower layers
+ * first, and given up, later layers first; with several announced sessions only their lower layers may be resident).
+ * `slots` describes ONE pool of slots with n_layers = 1: a slot holds a block of any layer (symph_pool.h hands the
+ * slot numbers out).  Unit u is one layer of one session: d_unit_lens[u] tokens, token t in slot
+ * d_unit_table[u][t / block_size]; in the buffer its K rows start at row d_unit_chunk_rows[u] (rows of
+ * n_kv_heads * head_dim elements) and its V rows d_unit_lens[u] rows later, which is where layer l of session s lies
+ * in a whole migration buffer when chunk_rows = off[s] * 2 * L + 2 * l * P_s.  d_unit_token_offsets [n_units+1] is the
+ * exclusive prefix sum of the lengths (it splits the launch's work), total_unit_tokens its last entry.  All units go
+ * in one launch; nothing else in the pool or the buffer is touched; a unit whose chunk would pass buf_bytes, or with a
+ * negative chunk row, is skipped.  buf_bytes is the size of the whole buffer (at least 2 * total_unit_tokens rows).
+ */
+int32_t symph_kv_pack_units(const symph_kv_cache* slots, const int32_t* d_unit_table, int32_t table_stride,
+                            const int32_t* d_unit_lens, const int64_t* d_unit_token_offsets,
+                            const int64_t* d_unit_chunk_rows, int32_t n_units, int64_t total_unit_tokens, void* d_buf,
+                            int64_t buf_bytes, void* stream);
+int32_t symph_kv_unpack_units(const symph_kv_cache* slots, const int32_t* d_unit_table, int32_t table_stride,
+                              const int32_t* d_unit_lens, const int64_t* d_unit_token_offsets,
+                              const int64_t* d_unit_chunk_rows, int32_t n_units, int64_t total_unit_tokens,
+                              const void* d_buf, int64_t buf_bytes, void* stream);
+
 /* Plain contiguous device copy with the same 16-byte-per-lane access shape as pack / unpack: the practical
  * HBM ceiling the migration kernels are compared with, and the known-size kernel used to calibrate hardware
  * traffic counters.  bytes must be a multiple of 16, pointers 16-byte aligned. */

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     kv_unpack_layers,
     kv_pack_tail,
     kv_unpack_tail,
+    kv_pack_units,
+    kv_unpack_units,
     kv_append,
     prefix_prefill_attn,
     prefix_prefill_attn_workspace_bytes,

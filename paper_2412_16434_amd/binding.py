@@ -15,7 +15,7 @@ SYMPH_BF16, SYMPH_FP32 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
-    "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_append",
+    "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_pack_units", "symph_kv_unpack_units", "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
     "symph_mfma_reference",
@@ -68,6 +68,9 @@ def load_library():
         fn.restype = i32
         fn.argtypes = [cp, i32, i32, vp, i32, vp, vp, i32, i64, vp, i64, vp]
     for fn in (lib.symph_kv_pack_tail, lib.symph_kv_unpack_tail):
+        fn.restype = i32
+        fn.argtypes = [cp, vp, i32, vp, vp, vp, i32, i64, vp, i64, vp]
+    for fn in (lib.symph_kv_pack_units, lib.symph_kv_unpack_units):
         fn.restype = i32
         fn.argtypes = [cp, vp, i32, vp, vp, vp, i32, i64, vp, i64, vp]
     for fn in (lib.symph_stage_layer_to_host, lib.symph_stage_layer_to_device):
@@ -219,6 +222,28 @@ def kv_unpack_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block
         dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
         prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
         "symph_kv_unpack_layers")
+
+
+def _units(fn_name, slots: KVCache, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens, buf,
+           stream):
+    st = slots.struct()
+    _check(getattr(load_library(), fn_name)(
+        C.byref(st), _ptr(unit_table), unit_table.shape[1] if unit_table.dim() == 2 else 0, _ptr(unit_lens),
+        _ptr(unit_token_offsets), _ptr(unit_chunk_rows), unit_lens.shape[0], int(total_unit_tokens), _ptr(buf),
+        buf.numel() * buf.element_size(), _stream_ptr(stream)), fn_name)
+
+
+def kv_pack_units(slots: KVCache, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens: int,
+                  buf, stream=None) -> None:
+    """Gather single layers of sessions from one pool of slots (a one-layer KVCache) into their chunks of ``buf``."""
+    _units("symph_kv_pack_units", slots, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens,
+           buf, stream)
+
+
+def kv_unpack_units(slots: KVCache, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens: int,
+                    buf, stream=None) -> None:
+    _units("symph_kv_unpack_units", slots, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows,
+           total_unit_tokens, buf, stream)
 
 
 def kv_pack_tail(cache: KVCache, block_table, prefix_lens, tail_begin, tail_offsets, total_tail_tokens: int, buf,

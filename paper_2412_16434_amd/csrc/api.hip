@@ -18,7 +18,8 @@ int32_t validate_cache(const symph_kv_cache* c) {
 static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
                        const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
                        const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
-                       int64_t buf_bytes, void* stream, const int32_t* d_tail_begin = nullptr) {
+                       int64_t buf_bytes, void* stream, const int32_t* d_tail_begin = nullptr,
+                       const int64_t* d_chunk_rows = nullptr) {
   int32_t rc = validate_cache(cache);
   if (rc != SYMPH_OK) return rc;
   if (n_sessions < 0 || total_tokens < 0 || table_stride < 0 || buf_bytes < 0) return SYMPH_EINVAL;
@@ -29,7 +30,19 @@ static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_beg
   if (need < 0) return SYMPH_EINVAL;
   if (buf_bytes < need) return SYMPH_EWORKSPACE;
   return launch_kv_migrate(pack, cache, layer_begin, layer_end, d_table, table_stride, d_prefix_lens, d_tail_begin,
-                           d_offsets, n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream);
+                           d_offsets, n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream, d_chunk_rows);
+}
+
+// Units (single layers of sessions) between one pool of slots and chunks placed anywhere in the buffer.
+static int32_t migrate_units(bool pack, const symph_kv_cache* slots, const int32_t* d_table, int32_t table_stride,
+                             const int32_t* d_unit_lens, const int64_t* d_unit_token_offsets,
+                             const int64_t* d_unit_chunk_rows, int32_t n_units, int64_t total_unit_tokens, void* d_buf,
+                             int64_t buf_bytes, void* stream) {
+  if (!slots) return SYMPH_EINVAL;
+  if (slots->n_layers != 1) return SYMPH_EINVAL;  // the slot pool has no layer axis: a slot holds a block of any layer
+  if (n_units > 0 && total_unit_tokens > 0 && !d_unit_chunk_rows) return SYMPH_EINVAL;
+  return migrate(pack, slots, 0, 1, d_table, table_stride, d_unit_lens, d_unit_token_offsets, n_units,
+                 total_unit_tokens, d_buf, buf_bytes, stream, nullptr, d_unit_chunk_rows);
 }
 
 // The chunk of one layer of one session in the migration buffer (bytes): 2 * P rows of K then V.
@@ -115,6 +128,22 @@ int32_t symph_kv_unpack_tail(const symph_kv_cache* cache, const int32_t* d_dst_b
   if (n_sessions > 0 && total_tail_tokens > 0 && !d_tail_begin) return SYMPH_EINVAL;
   return migrate(false, cache, 0, cache->n_layers, d_dst_block_table, table_stride, d_prefix_lens, d_tail_offsets,
                  n_sessions, total_tail_tokens, const_cast<void*>(d_buf), buf_bytes, stream, d_tail_begin);
+}
+
+int32_t symph_kv_pack_units(const symph_kv_cache* slots, const int32_t* d_unit_table, int32_t table_stride,
+                            const int32_t* d_unit_lens, const int64_t* d_unit_token_offsets,
+                            const int64_t* d_unit_chunk_rows, int32_t n_units, int64_t total_unit_tokens, void* d_buf,
+                            int64_t buf_bytes, void* stream) {
+  return migrate_units(true, slots, d_unit_table, table_stride, d_unit_lens, d_unit_token_offsets, d_unit_chunk_rows,
+                       n_units, total_unit_tokens, d_buf, buf_bytes, stream);
+}
+
+int32_t symph_kv_unpack_units(const symph_kv_cache* slots, const int32_t* d_unit_table, int32_t table_stride,
+                              const int32_t* d_unit_lens, const int64_t* d_unit_token_offsets,
+                              const int64_t* d_unit_chunk_rows, int32_t n_units, int64_t total_unit_tokens,
+                              const void* d_buf, int64_t buf_bytes, void* stream) {
+  return migrate_units(false, slots, d_unit_table, table_stride, d_unit_lens, d_unit_token_offsets, d_unit_chunk_rows,
+                       n_units, total_unit_tokens, const_cast<void*>(d_buf), buf_bytes, stream);
 }
 
 int32_t symph_kv_unpack(const symph_kv_cache* cache, const int32_t* d_dst_block_table, int32_t table_stride,

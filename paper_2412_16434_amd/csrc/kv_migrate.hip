@@ -35,6 +35,8 @@ struct MigrateParams {
   const int32_t* tail_begin;  // null: whole sessions; else only tokens tail_begin[s] .. prefix_lens[s]-1 move, and
                               // offsets / total_tokens count those
   const int64_t* offsets;
+  const int64_t* chunk_rows;  // null: session s starts at row offsets[s] * n_planes of the buffer (whole-cache layout);
+                              // else at row chunk_rows[s] (units of one layer placed anywhere in a larger buffer)
   int32_t n_sessions;
   int64_t total_tokens;
   char* buf;
@@ -102,7 +104,12 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   if (b < 0 || b >= p.n_blocks) return;  // not a block of this cache: touch nothing
   const int32_t slot = t - j * p.block_size;
   const int64_t plane_b = (int64_t)P * p.row_bytes;  // one (layer, K|V) plane of this session in the buffer
-  const int64_t sess_b = off_s * p.n_planes * p.row_bytes;
+  int64_t sess_b = off_s * p.n_planes * p.row_bytes;
+  if (p.chunk_rows) {
+    const int64_t first_row = p.chunk_rows[s];
+    if (first_row < 0 || first_row > p.buf_bytes / p.row_bytes) return;  // (the second test also keeps the product in range)
+    sess_b = first_row * p.row_bytes;
+  }
   if (sess_b + plane_b * p.n_planes > p.buf_bytes) return;  // the session would not fit the buffer: touch nothing
 
   const int64_t pool_off = (int64_t)b * p.block_stride_b + (int64_t)slot * p.row_bytes + (int64_t)col * sizeof(VecT);
@@ -179,7 +186,8 @@ static int log2_or_neg(int64_t x) { return (x > 0 && (x & (x - 1)) == 0) ? __bui
 int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begin, int32_t layer_end,
                           const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
                           const int32_t* d_tail_begin, const int64_t* d_offsets, int32_t n_sessions,
-                          int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream) {
+                          int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream,
+                          const int64_t* d_chunk_rows) {
   const int eb = elem_bytes_of(c->dtype);
   const int64_t row_bytes = (int64_t)c->n_kv_heads * c->head_dim * eb;
   if (row_bytes > 0x7FFFFFFF) return SYMPH_EUNSUPPORTED;
@@ -210,6 +218,7 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begi
   p.prefix_lens = d_prefix_lens;
   p.tail_begin = d_tail_begin;
   p.offsets = d_offsets;
+  p.chunk_rows = d_chunk_rows;
   p.n_sessions = n_sessions;
   p.total_tokens = total_tokens;
   p.buf = (char*)d_buf;

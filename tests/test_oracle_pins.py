@@ -615,23 +615,9 @@ def test_unpack_tail_touches_the_tail_slots_only(oracle_mod):
 # --------------------------------------------------------------------------------------------------------
 # unit-wise copies: single layers of sessions in one pool of slots (Sec. 3.3, priority-based K,V cache)
 # --------------------------------------------------------------------------------------------------------
-def random_units(rng, n_units, n_slots, bs, max_len, row, gap_rows=3):
-    """Units with disjoint random slot tables and chunks placed in random order with gaps in one buffer."""
-    lens = rng.integers(0, max_len + 1, size=n_units).astype(np.int32)
-    nbs = -(-lens // bs)
-    perm = rng.permutation(n_slots)[: int(nbs.sum())].astype(np.int32)
-    stride = max(int(nbs.max()), 1) + 1
-    table = np.full((n_units, stride), -7, dtype=np.int32)
-    at = 0
-    for u in range(n_units):
-        table[u, : nbs[u]] = perm[at: at + nbs[u]]
-        at += nbs[u]
-    chunk_rows = np.zeros(n_units, dtype=np.int64)
-    row_at = 2
-    for u in rng.permutation(n_units):
-        chunk_rows[u] = row_at
-        row_at += 2 * int(lens[u]) + int(rng.integers(0, gap_rows + 1))
-    return lens, table, chunk_rows, row_at + 1
+def random_units(rng, n_units, n_slots, bs, max_len, row):
+    ub = W.make_units(rng, n_units, n_slots, bs, max_len)
+    return ub.unit_lens, ub.unit_table, ub.unit_chunk_rows, ub.n_buf_rows
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])

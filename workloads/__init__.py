@@ -15,7 +15,7 @@ Two kinds of values are produced:
   bytes, so any bit pattern, NaN payloads included, is a valid input).
 """
 from .configs import WorkloadConfig, CONFIGS, get_config, scaled_config
-from .sessions import SessionBatch, make_sessions
+from .sessions import SessionBatch, UnitBatch, make_sessions, make_units
 from .values import (
     f32_to_bf16_bits,
     bf16_bits_to_f32,
@@ -29,7 +29,7 @@ from .values import (
 
 __all__ = [
     "WorkloadConfig", "CONFIGS", "get_config", "scaled_config",
-    "SessionBatch", "make_sessions",
+    "SessionBatch", "UnitBatch", "make_sessions", "make_units",
     "f32_to_bf16_bits", "bf16_bits_to_f32", "counter_bits_host", "counter_bits_device",
     "make_attn_inputs", "make_pool_host", "fill_pool_blocks_device", "SENTINEL16",
 ]

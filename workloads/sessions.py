@@ -157,3 +157,45 @@ def make_sessions(cfg: WorkloadConfig, seed: Optional[int] = None) -> SessionBat
     cu = np.zeros(S + 1, dtype=np.int32)
     cu[1:] = np.cumsum(new.astype(np.int64)).astype(np.int32)
     return SessionBatch(cfg, prefix, new, table, dst, off, cu)
+
+
+@dataclass
+class UnitBatch:
+    """Single layers of sessions ("units") that live in one pool of slots and in chunks of a larger buffer."""
+    unit_lens: np.ndarray          # int32 [U] tokens per unit
+    unit_table: np.ndarray         # int32 [U][stride] slot of every block, unused entries negative
+    unit_chunk_rows: np.ndarray    # int64 [U] first row (K rows, then as many V rows) in the buffer
+    unit_token_offsets: np.ndarray # int64 [U+1] exclusive prefix sum of unit_lens
+    n_buf_rows: int
+
+    @property
+    def n_units(self) -> int:
+        return int(self.unit_lens.shape[0])
+
+    @property
+    def total_tokens(self) -> int:
+        return int(self.unit_token_offsets[-1])
+
+
+def make_units(rng: np.random.Generator, n_units: int, n_slots: int, block_size: int, max_len: int, min_len: int = 0,
+               max_gap_rows: int = 3) -> UnitBatch:
+    """Units of random length with disjoint random slot tables; their chunks lie in random order, with random gaps,
+    in one buffer of ``n_buf_rows`` rows."""
+    lens = rng.integers(min_len, max_len + 1, size=n_units).astype(np.int32)
+    nbs = -(-lens // block_size)
+    if int(nbs.sum()) > n_slots:
+        raise ValueError("pool too small for these units")
+    perm = rng.permutation(n_slots)[: int(nbs.sum())].astype(np.int32)
+    stride = max(int(nbs.max()) if n_units else 0, 1) + 1
+    table = np.full((n_units, stride), -7, dtype=np.int32)
+    at = 0
+    for u in range(n_units):
+        table[u, : nbs[u]] = perm[at: at + nbs[u]]
+        at += int(nbs[u])
+    chunk_rows = np.zeros(n_units, dtype=np.int64)
+    row_at = 2
+    for u in rng.permutation(n_units):
+        chunk_rows[u] = row_at
+        row_at += 2 * int(lens[u]) + int(rng.integers(0, max_gap_rows + 1))
+    offsets = np.concatenate([[0], np.cumsum(lens.astype(np.int64))]).astype(np.int64)
+    return UnitBatch(lens, table, chunk_rows, offsets, row_at + 1)
