@@ -570,6 +570,33 @@ def main():
     torch.cuda.synchronize()
     tail_ms = e0.elapsed_time(e1) / 10
 
+    # ---- priority-based residency (Sec. 3.3): the LOWER HALF of the layers of every session moved in with one launch.
+    # The same pools seen as one pool of L * n_blocks slots (slot = layer * n_blocks + block), one unit per (session,
+    # layer), the chunks where they lie in the whole migration buffer.
+    Lh = max(cfg.n_layers // 2, 1)
+    nb_pool = k_pool.shape[1]
+    slot_pool = S.KVCache(k_pool.view(1, cfg.n_layers * nb_pool, *k_pool.shape[2:]),
+                          v_pool.view(1, cfg.n_layers * nb_pool, *v_pool.shape[2:]))
+    units = [(s_, l_) for l_ in range(Lh) for s_ in range(sess.n_sessions)]
+    u_lens_h = np.array([sess.prefix_lens[s_] for s_, _ in units], dtype=np.int32)
+    u_table_h = np.stack([np.where(sess.dst_block_table[s_] >= 0, sess.dst_block_table[s_] + l_ * nb_pool, -1)
+                          for s_, l_ in units]).astype(np.int32)
+    u_rows_h = np.array([int(sess.buf_token_offsets[s_]) * 2 * cfg.n_layers + 2 * l_ * int(sess.prefix_lens[s_])
+                         for s_, l_ in units], dtype=np.int64)
+    u_off_h = np.concatenate([[0], np.cumsum(u_lens_h.astype(np.int64))]).astype(np.int64)
+    u_table, u_lens, u_off, u_rows = (torch.from_numpy(a).to(dev) for a in (u_table_h, u_lens_h, u_off_h, u_rows_h))
+    u_total = int(u_off_h[-1])
+    u_payload = 2 * u_total * cfg.n_kv_heads * cfg.head_dim * 2
+    for _ in range(2):
+        S.kv_unpack_units(slot_pool, u_table, u_lens, u_off, u_rows, u_total, buf)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        S.kv_unpack_units(slot_pool, u_table, u_lens, u_off, u_rows, u_total, buf)
+    e1.record()
+    torch.cuda.synchronize()
+    units_ms = e0.elapsed_time(e1) / 10
+
     # ---- MFMA-only reference kernel: what the matrix cores deliver here, for a launch as short as the attention
     # call (the shader clock is still ramping up) and sustained ------------------------------------------------------
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
@@ -642,6 +669,9 @@ def main():
         "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
         "kv_pack_tail_new_turn": {"ms": tail_ms, "GBps": 2.0 * tail_payload / tail_ms / 1e6, "payload_bytes": tail_payload,
                                   "pct_hbm_peak": 100 * 2.0 * tail_payload / tail_ms / 1e6 / HBM_PEAK_GBS},
+        "kv_unpack_units_lower_half_of_the_layers": {"ms": units_ms, "GBps": 2.0 * u_payload / units_ms / 1e6,
+                                                     "payload_bytes": u_payload, "n_units": len(units),
+                                                     "pct_hbm_peak": 100 * 2.0 * u_payload / units_ms / 1e6 / HBM_PEAK_GBS},
         "mfma_reference": {**mfma_ref, "attn_pct_of_short_reference": 100 * attn_tflops / mfma_ref["short"]["TFLOPs"]},
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
