@@ -597,6 +597,36 @@ def main():
     torch.cuda.synchronize()
     units_ms = e0.elapsed_time(e1) / 10
 
+    # ---- the residency pool itself (host code, Sec. 3.3): 512 announced sessions of config-2 lengths, 32 layers, room for
+    # a quarter of them; time of one settle from empty, of a framework demand that evicts, of the settle after it
+    rng_pool = np.random.default_rng(12)
+    pool_lens = rng_pool.integers(1024, 8193, size=512)
+    pool_blocks = int(np.sum(-(-pool_lens // cfg.block_size))) * cfg.n_layers
+    kp = S.KvPool(cfg.n_layers, pool_blocks // 4, cfg.block_size)
+    for i, n in enumerate(pool_lens):
+        kp.advise(i, int(n))
+    import ctypes as C
+    from paper_2412_16434_amd.binding import _PoolChange
+    lib, n_take = S.load_library(), pool_blocks // 16
+    changes = (_PoolChange * (512 * cfg.n_layers))()
+    slot_arr = (C.c_int32 * (pool_blocks // 4))()
+    take_arr = (C.c_int32 * n_take)()
+    nc, ns = C.c_int32(), C.c_int32()
+    t0 = time.perf_counter()
+    rc0 = lib.symph_pool_settle(kp._h, changes, len(changes), slot_arr, len(slot_arr), C.byref(nc), C.byref(ns))
+    t1 = time.perf_counter()
+    loaded = nc.value
+    rc1 = lib.symph_pool_framework_take(kp._h, n_take, take_arr)
+    t2 = time.perf_counter()
+    rc2 = lib.symph_pool_settle(kp._h, changes, len(changes), slot_arr, len(slot_arr), C.byref(nc), C.byref(ns))
+    t3 = time.perf_counter()
+    assert rc0 == rc1 == rc2 == 0
+    pool_stats = {"sessions": 512, "layers": cfg.n_layers, "slots": pool_blocks // 4,
+                  "first_settle_ms": (t1 - t0) * 1e3, "units_loaded": loaded, "slots_assigned": pool_blocks // 4 - kp.counts()[0] - n_take,
+                  "framework_take_ms": (t2 - t1) * 1e3, "slots_taken": n_take,
+                  "settle_after_it_ms": (t3 - t2) * 1e3, "changes_reported": nc.value}
+    kp.close()
+
     # ---- MFMA-only reference kernel: what the matrix cores deliver here, for a launch as short as the attention
     # call (the shader clock is still ramping up) and sustained ------------------------------------------------------
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
@@ -672,6 +702,7 @@ def main():
         "kv_unpack_units_lower_half_of_the_layers": {"ms": units_ms, "GBps": 2.0 * u_payload / units_ms / 1e6,
                                                      "payload_bytes": u_payload, "n_units": len(units),
                                                      "pct_hbm_peak": 100 * 2.0 * u_payload / units_ms / 1e6 / HBM_PEAK_GBS},
+        "residency_pool_host": pool_stats,
         "mfma_reference": {**mfma_ref, "attn_pct_of_short_reference": 100 * attn_tflops / mfma_ref["short"]["TFLOPs"]},
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
