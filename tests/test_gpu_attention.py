@@ -180,7 +180,7 @@ def test_peaked_attention_with_position_coded_values(oracle_mod, dtype):
     check(oracle_mod, cfg, sess, (k_pool, v_pool, q, k_new, v_new), label="peaked")
 
 
-@pytest.mark.parametrize("shape", ["rising", "falling", "spike", "late_giant"])
+@pytest.mark.parametrize("shape", ["rising", "falling", "spike", "late_giant", "threshold", "low_then_high"])
 def test_score_ranges_that_move_the_softmax_reference(oracle_mod, shape):
     """Scores whose level changes by tens to hundreds of powers of two between key tiles: every key is a multiple
     of one direction u and every query is u, so score(key j) = |u|^2 * amp(j).  A kernel that keeps a softmax
@@ -205,6 +205,12 @@ def test_score_ranges_that_move_the_softmax_reference(oracle_mod, shape):
                 amp = 2.0 * (total // 64 + 1 - t)
             elif shape == "spike":
                 amp = 24.0 if j % 97 == 50 else 0.25 * (j % 5)     # isolated keys ~550 powers of two above the rest
+            elif shape == "threshold":
+                # levels of 23.08 * amp powers of two: just below and just above 20 (where a kernel may switch between
+                # a zero and a non-zero reference), both signs, then far above
+                amp = [0.85, 0.9, -0.9, 0.86, -0.85, 2.5, 0.1, 0.88][(t + s) % 8]
+            elif shape == "low_then_high":
+                amp = -0.8 if t < 3 else (0.9 if t < 5 else 2.0)   # -18, then +21, then +46 powers of two
             else:
                 amp = 60.0 if j >= total - 3 else 0.5              # the last keys of the turn dwarf everything
             row = enc(np.tile(u * amp, (cfg.n_kv_heads, 1)))
