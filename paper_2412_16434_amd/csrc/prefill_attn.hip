@@ -416,7 +416,6 @@ __device__ __forceinline__ void dev_trace_end(const MfmaParams& p, int tiles, in
 constexpr int kD = 128;  // head_dim
 // A row sum above this (one probability of 2^40 or more, or an overflow) makes the softmax reference stale.
 constexpr float kRefreshSum = 1.0995116e12f;  // 2^40
-constexpr float kZeroRefLog2 = 20.f;          // a maximum within +-this keeps the reference at zero (attn_mfma_kernel)
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -548,11 +547,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) qreg[st][e] = (__bf16)0.0f;
       }
-      // The scale (times log2 e) goes into Q once, so that the first product delivers exponents of two directly; the
-      // price is one more rounding of Q to bf16 (relative 2^-9 per element, i.e. ~1e-3 * |score| / sqrt(d) in the
-      // exponent, well below the rounding of the probabilities).
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qreg[st][e] = (__bf16)((float)qreg[st][e] * p.scale_log2e);
     }
   }
 
@@ -661,9 +655,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o_acc[dt][e] = 0.f;
-  float m_run = -INFINITY;  // maximum of the scores when the reference was last looked at, in log2 units (scale and
-                            // log2 e are inside Q); -inf: the row has seen no key yet
+  float m_run = -INFINITY;  // running max of raw scores (before scale)
   float l_run = 0.f;        // this lane's share of the running sum
+  const float cs = p.scale_log2e;
   const int q_limit = P + tok;  // last key this query may see
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
@@ -703,13 +697,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // softmax as long as nothing overflows, and bf16 / fp32 keep their relative precision at any magnitude.  The
   // reference is refreshed (below) only when a tile's row sum shows that some score exceeds it by more than
   // kRefreshLog2, which after the first tile practically never happens; the per-tile maximum, the rescale factor
-  // and the rescaling of the accumulators thereby leave the loop.  And the reference is ZERO whenever the maximum it
-  // would be taken from lies within +-kZeroRefLog2 (any reference that far from the maximum serves as well): the first
-  // product then delivers the argument of the exponential as it is, with no vector instruction per score for "scale
-  // and subtract"; a wave with a non-zero reference in some lane subtracts it in a branch of its own.
+  // and the rescaling of the accumulators thereby leave the loop.
   // reference := max(reference, maximum of this tile), in log2 units; returns the factor by which everything
   // accumulated so far has to be rescaled (0 for a first reference, 1 where nothing moved)
-  // (the scores are relative to the present reference mb)
   auto raise_reference = [&](const f32x16 (&sc)[2], float& mb) {
     float mx = sc[0][0];
 #pragma unroll
@@ -717,24 +707,22 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[kb][e]);
     mx = max_across_halves(mx);
-    const float m_new = fmaxf(m_run, mx + mb);
+    const float m_new = fmaxf(m_run, mx * cs);
     // a row that has seen no key yet (a work item may start past its causal limit) keeps m_run = -inf, which the
     // merge step reads as "no contribution"; its exponent arguments use 0 so that they stay finite
-    const float mb_new = (m_new == -INFINITY || fabsf(m_new) <= kZeroRefLog2) ? 0.f : m_new;
-    // what has been accumulated is relative to the old reference (nothing has been, for a row without a key so far)
-    const float a = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mb - mb_new);
+    const float a = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
-    mb = mb_new;
+    mb = (m_new == -INFINITY) ? 0.f : m_new;
     return a;
   };
   // ... then the bf16 probabilities, one 32-key half at a time: the first half follows the statistics directly (in
   // the block that is otherwise almost pure matrix work), the second half runs beside the next tile's first product,
   // so that both blocks of the pipeline carry a similar mix of matrix and vector work whatever block the other
   // workgroup of the CU happens to be in
-  auto softmax_exp_half = [&](const f32x16& sc, bf16x8 (&pb)[2]) {
+  auto softmax_exp_half = [&](const f32x16& sc, float mb, bf16x8 (&pb)[2]) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      pb[e >> 3][e & 7] = (__bf16)__builtin_amdgcn_exp2f(sc[e]);
+      pb[e >> 3][e & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[e], cs, -mb));
     }
   };
   // row sum of the ROUNDED probabilities (the values the second product uses), two per instruction
@@ -753,26 +741,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     return ps0 + ps1;
   };
   // Refresh of a stale reference (rare): rescale what has been accumulated, redo this tile's probabilities.
-  // Scores in registers are kept RELATIVE to the lane's reference.  shift_scores brings a tile to another reference
-  // (-inf of a masked key stays -inf: the references are finite).
-  auto shift_scores = [&](f32x16 (&sc)[2], float shift) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sc[kb][e] += shift;
-  };
-  auto refresh_reference = [&](f32x16 (&sc)[2], f32x16 (&sc_next)[2], float& mb, bf16x8 (&pb)[2][2], float& ps) {
-    const float mb_old = mb;
+  auto refresh_reference = [&](const f32x16 (&sc)[2], float& mb, bf16x8 (&pb)[2][2], float& ps) {
     const float a = raise_reference(sc, mb);
-    shift_scores(sc, mb_old - mb);
-    shift_scores(sc_next, mb_old - mb);   // the next tile's scores are in registers already, against the old reference
     l_run *= a;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) o_acc[dt][e] *= a;
-    softmax_exp_half(sc[0], pb[0]);
-    softmax_exp_half(sc[1], pb[1]);
+    softmax_exp_half(sc[0], mb, pb[0]);
+    softmax_exp_half(sc[1], mb, pb[1]);
     ps = row_sum(pb);
   };
   auto wait_loads_and_sync = [&]() {
@@ -813,12 +790,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
   fetch_ids(tile_begin + 2);                      // taken at the top of the first iteration
-  float mb_cur = 0.f;  // reference of the exponentials, in log2 units (the first product ran against 0)
-  bf16x8 pb[2][2];     // P(j); its first half is produced one block ahead of the second
+  float mb_cur;     // reference of the exponentials, in log2 units
+  bf16x8 pb[2][2];  // P(j); its first half is produced one block ahead of the second
   mask(s_even, tile_begin);
-  raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile, or zero
-  if (__any(mb_cur != 0.f)) shift_scores(s_even, -mb_cur);
-  softmax_exp_half(s_even[0], pb[0]);
+  raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile
+  softmax_exp_half(s_even[0], mb_cur, pb[0]);
 
   auto iteration = [&](const int j, auto par_c) {
     constexpr int PAR = decltype(par_c)::value;
@@ -845,14 +821,14 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #endif
     // ---- block A
     qk(k_other, s_nxt);                          // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
-    softmax_exp_half(s_cur[1], pb[1]);           // second half of P(j)
+    softmax_exp_half(s_cur[1], mb_cur, pb[1]);   // second half of P(j)
     float ps = row_sum(pb);
     __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);      // K fragments: six reads up front
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA of S(j+1)
       if (g < 10) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);    // vector ALU: convert, sum
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);    // vector ALU: scale, convert, sum
       __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);    // one exponential
     }
     // keep the probabilities (and with them the exponentials) in this block: without a use here the compiler sinks
@@ -869,8 +845,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     // The reference is stale when some score exceeds it by more than 40 in log2 units (then the row sum is huge,
     // infinite or NaN), or when a row that had seen no key now has one.  Rare: redo this tile's probabilities from
     // its scores, which are still in registers, against a refreshed reference.
-    if (__any(mb_cur != 0.f)) shift_scores(s_nxt, -mb_cur);   // rare: the first product starts from zero
-    if (__any(!(ps <= kRefreshSum) || (m_run == -INFINITY && ps > 0.f))) refresh_reference(s_cur, s_nxt, mb_cur, pb, ps);
+    if (__any(!(ps <= kRefreshSum) || (m_run == -INFINITY && ps > 0.f))) refresh_reference(s_cur, mb_cur, pb, ps);
     l_run += ps;
     mask(s_nxt, j + 1);
     // ---- block B
@@ -894,7 +869,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       for (int g = 0; g < 16; ++g) {
         if (g + 4 < 16) frag[g + 4] = v_frag(g + 4);
         o_acc[g & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[g], pb[g >> 3][(g >> 2) & 1], o_acc[g & 3], 0, 0, 0);
-        pe[g] = __builtin_amdgcn_exp2f(s_nxt[0][g]);
+        pe[g] = __builtin_amdgcn_exp2f(fmaf(s_nxt[0][g], cs, -mb_cur));
         asm volatile("" : "+v"(pe[g]));  // evaluated in this slot (a value without side effects is otherwise placed
                                          // next to its use, after the last slot)
         if (g & 1) {
@@ -953,7 +928,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) part[(dt * 16 + e) * 256] = o_acc[dt][e];
-    part[64 * 256] = (m_run == -INFINITY) ? -INFINITY : mb_cur;   // what l_run and o_acc are relative to
+    part[64 * 256] = m_run;
     part[65 * 256] = l_run;
   }
 #if SYMPH_DEV_TIMERS

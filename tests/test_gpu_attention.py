@@ -222,6 +222,20 @@ def test_score_ranges_that_move_the_softmax_reference(oracle_mod, shape):
     check(oracle_mod, cfg, sess, (k_pool, v_pool, q, k_new, v_new), label=shape)
 
 
+@pytest.mark.parametrize("scale", [0.35, 1.0, 2.5])
+@pytest.mark.parametrize("kind", ["prefill", "decode"])
+def test_large_score_magnitudes(oracle_mod, scale, kind):
+    """Unit-variance Q and K with scales far above 1/sqrt(d): scores of +-10 .. +-80 powers of two, a softmax that sits
+    on one or two keys per row, outputs of magnitude ~1.  Any extra rounding of Q, K or of the scaled scores shows
+    here long before it does at the nominal scale (a variant that rounded Q * scale to bf16 reached 0.14 at scale 1.0
+    where the tolerance is 0.02)."""
+    new_dist = ("uniform", 1, 150) if kind == "prefill" else ("uniform", 1, 8)
+    cfg = _cfg(n_sessions=14, n_q_heads=8, n_kv_heads=2, prefix_dist=("uniform", 1, 1500), new_dist=new_dist,
+               n_blocks=2048, scale=scale)
+    sess = W.make_sessions(cfg, 23)
+    check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 23), label=f"scale {scale} {kind}")
+
+
 def test_constant_values_per_session(oracle_mod):
     cfg = _cfg(n_sessions=6, prefix_dist=("uniform", 10, 200), new_dist=("uniform", 1, 50))
     sess = W.make_sessions(cfg, 8)
