@@ -9,8 +9,9 @@
  *
  * Conventions for every entry point
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers; everything else is passed by value.
- *   - The caller owns every buffer.  The library allocates no memory and keeps no state between calls; calls may
- *     be issued concurrently on different streams as long as the memory they write does not overlap.
+ *   - The caller owns every buffer.  The library allocates no memory (symph_debug_check_tables aside) and keeps no
+ *     state between calls; calls may be issued concurrently on different streams as long as the memory they write
+ *     does not overlap.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work and return
  *     without synchronising; device arrays must stay valid until the stream has executed the work.
  *   - Return value: SYMPH_OK or a negative symph_status.  Nothing aborts or throws across the ABI.  Host-visible
@@ -224,6 +225,19 @@ int32_t symph_kv_unpack_units(const symph_kv_cache* slots, const int32_t* d_unit
                               const int32_t* d_unit_lens, const int64_t* d_unit_token_offsets,
                               const int64_t* d_unit_chunk_rows, int32_t n_units, int64_t total_unit_tokens,
                               const void* d_buf, int64_t buf_bytes, void* stream);
+
+/*
+ * Optional check of what the kernels take on trust (the caller's contract on device-resident contents): every length
+ * is >= 0 and fits its table row, every block id a session uses lies in [0, n_blocks), and - for a destination table
+ * (is_destination != 0: unpack, append) - no block is named twice, within a session or across sessions.  d_lens are
+ * the lengths the table has to cover (prefix lengths, or prefix + new-turn lengths before an append).  A debugging
+ * aid, unlike every other entry point: it copies both arrays to host memory it allocates for the call and
+ * synchronises `stream`.  Returns SYMPH_OK, or SYMPH_EINVAL with the first offending session in *h_first_bad_session
+ * (may be null; -1 if the arguments themselves were invalid).
+ */
+int32_t symph_debug_check_tables(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
+                                 const int32_t* d_lens, int32_t n_sessions, int32_t is_destination, void* stream,
+                                 int32_t* h_first_bad_session);
 
 /* Plain contiguous device copy with the same 16-byte-per-lane access shape as pack / unpack: the practical
  * HBM ceiling the migration kernels are compared with, and the known-size kernel used to calibrate hardware

@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     stage_layer_to_device,
     device_copy,
     mfma_reference,
+    debug_check_tables,
     status_string,
     EXPORTED_SYMBOLS,
 )

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = (
     "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_pack_units", "symph_kv_unpack_units", "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
-    "symph_mfma_reference",
+    "symph_mfma_reference", "symph_debug_check_tables",
     "symph_status_string",
     # symph_pool.h (host code only)
     "symph_pool_create", "symph_pool_destroy", "symph_pool_advise", "symph_pool_drop", "symph_pool_claim",
@@ -90,6 +90,8 @@ def load_library():
     lib.symph_device_copy.argtypes = [vp, vp, i64, vp]
     lib.symph_mfma_reference.restype = i32
     lib.symph_mfma_reference.argtypes = [i32, C.POINTER(C.c_int64), vp, vp]
+    lib.symph_debug_check_tables.restype = i32
+    lib.symph_debug_check_tables.argtypes = [cp, vp, i32, vp, i32, i32, vp, C.POINTER(i32)]
     lib.symph_status_string.restype = C.c_char_p
     lib.symph_status_string.argtypes = [i32]
     ip = C.POINTER(i32)
@@ -244,6 +246,18 @@ def kv_unpack_units(slots: KVCache, unit_table, unit_lens, unit_token_offsets, u
                     buf, stream=None) -> None:
     _units("symph_kv_unpack_units", slots, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows,
            total_unit_tokens, buf, stream)
+
+
+def debug_check_tables(cache: KVCache, block_table, lens, is_destination: bool, stream=None) -> int:
+    """-1 if the table and lengths keep the contract the kernels rely on, else the first offending session."""
+    st = cache.struct()
+    bad = C.c_int32(-1)
+    rc = load_library().symph_debug_check_tables(
+        C.byref(st), _ptr(block_table), block_table.shape[1] if block_table.dim() == 2 else 0, _ptr(lens),
+        lens.shape[0], 1 if is_destination else 0, _stream_ptr(stream), C.byref(bad))
+    if rc != 0 and bad.value < 0:
+        _check(rc, "symph_debug_check_tables")
+    return bad.value
 
 
 def kv_pack_tail(cache: KVCache, block_table, prefix_lens, tail_begin, tail_offsets, total_tail_tokens: int, buf,

@@ -1,6 +1,9 @@
 // extern "C" entry points: host-side validation, then launches. No allocation, no global state.
 #include "common.h"
 
+#include <new>
+#include <vector>
+
 namespace symph {
 
 int32_t validate_cache(const symph_kv_cache* c) {
@@ -281,6 +284,46 @@ int32_t symph_device_copy(void* d_dst, const void* d_src, int64_t bytes, void* s
   if (!d_dst || !d_src) return SYMPH_EINVAL;
   if ((bytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15)) return SYMPH_EUNSUPPORTED;
   return launch_device_copy(d_dst, d_src, bytes, (hipStream_t)stream);
+}
+
+int32_t symph_debug_check_tables(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,
+                                 const int32_t* d_lens, int32_t n_sessions, int32_t is_destination, void* stream,
+                                 int32_t* h_first_bad_session) {
+  if (h_first_bad_session) *h_first_bad_session = -1;
+  if (!cache || cache->n_blocks <= 0 || cache->block_size <= 0 || n_sessions < 0 || table_stride < 0) return SYMPH_EINVAL;
+  if (n_sessions == 0) return SYMPH_OK;
+  if (!d_block_table || !d_lens || table_stride == 0) return SYMPH_EINVAL;
+  try {
+    std::vector<int32_t> lens((size_t)n_sessions), table((size_t)n_sessions * table_stride);
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(lens.data(), d_lens, lens.size() * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemcpyAsync(table.data(), d_block_table, table.size() * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+      return SYMPH_ELAUNCH;
+    std::vector<uint8_t> taken;
+    if (is_destination) taken.assign((size_t)cache->n_blocks, 0);
+    for (int32_t s = 0; s < n_sessions; ++s) {
+      bool bad = lens[s] < 0;
+      const int64_t nb = bad ? 0 : ceil_div64(lens[s], cache->block_size);
+      if (nb > table_stride) bad = true;
+      for (int64_t j = 0; j < nb && !bad; ++j) {
+        const int32_t b = table[(size_t)s * table_stride + j];
+        if (b < 0 || b >= cache->n_blocks) {
+          bad = true;
+        } else if (is_destination) {
+          if (taken[b]) bad = true;
+          taken[b] = 1;
+        }
+      }
+      if (bad) {
+        if (h_first_bad_session) *h_first_bad_session = s;
+        return SYMPH_EINVAL;
+      }
+    }
+  } catch (const std::bad_alloc&) {
+    return SYMPH_ENOMEM;
+  }
+  return SYMPH_OK;
 }
 
 int32_t symph_mfma_reference(int32_t iters, int64_t* h_flops, void* d_sink, void* stream) {

@@ -96,6 +96,9 @@ def test_host_validation_rejects_without_launching():
     assert lib.symph_kv_unpack_units(C.byref(one), 0x10, 4, 0x10, 0x10, None, 1, 8, 0x10, 1 << 20, None) == EINVAL    # no chunk rows
     assert lib.symph_kv_pack_units(C.byref(one), 0x10, 4, 0x10, 0x10, 0x10, 1, 8, 0x10, 16, None) == EWS              # buffer too small
     assert lib.symph_kv_pack_units(C.byref(one), None, 0, None, None, None, 0, 0, None, 0, None) == 0
+    assert lib.symph_debug_check_tables(None, 0x10, 4, 0x10, 1, 0, None, None) == EINVAL
+    assert lib.symph_debug_check_tables(C.byref(good), None, 4, 0x10, 1, 0, None, None) == EINVAL
+    assert lib.symph_debug_check_tables(C.byref(good), None, 0, None, 0, 1, None, None) == 0
     assert lib.symph_mfma_reference(0, None, 0x10, None) == EINVAL
     assert lib.symph_mfma_reference(8, None, None, None) == EINVAL
     assert S.status_string(0) == "ok" and "unsupported" in S.status_string(-2)

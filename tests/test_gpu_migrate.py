@@ -318,3 +318,36 @@ def _full_size_case(oracle_mod, cfg, n_sample=20000):
 def test_pack_unpack_full_size(oracle_mod, name):
     _full_size_case(oracle_mod, W.get_config(name))
     torch.cuda.empty_cache()
+
+
+def test_debug_check_tables_names_the_first_session_that_breaks_the_contract():
+    """The optional validator: clean tables pass; an id outside the cache, a table row too narrow for its length, a
+    negative length and (destination tables only) a block named twice are reported with the session they occur in."""
+    cfg = W.WorkloadConfig(name="chk", index=70, dtype="bf16", n_layers=1, n_q_heads=2, n_kv_heads=2, head_dim=16,
+                           block_size=16, n_blocks=64, n_sessions=5, prefix_dist=("uniform", 20, 90),
+                           new_dist=("const", 1), sigma=1.0, scale=0.1)
+    sess = W.make_sessions(cfg, 2)
+    pool = torch.zeros((1, cfg.n_blocks, cfg.block_size, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device=DEV)
+    cache = S.KVCache(pool, pool.clone())
+    lens = torch.from_numpy(sess.prefix_lens).to(DEV)
+
+    def run(table, lens_t=lens, dst=True):
+        return S.debug_check_tables(cache, torch.from_numpy(table).to(DEV), lens_t, dst)
+
+    good = sess.block_table.copy()
+    assert run(good) == -1 and run(good, dst=False) == -1
+    bad = good.copy(); bad[3, 1] = cfg.n_blocks                     # not a block of the cache
+    assert run(bad) == 3 and run(bad, dst=False) == 3
+    bad = good.copy(); bad[2, 0] = -1
+    assert run(bad) == 2
+    bad = good.copy(); bad[4, 0] = good[1, 0]                       # two writers for one block
+    assert run(bad) == 4 and run(bad, dst=False) == -1              # legal in a source table (shared prefix)
+    bad = good.copy(); bad[1, 1] = good[1, 0]                       # twice inside one session
+    assert run(bad) == 1
+    narrow = np.ascontiguousarray(good[:, :2])                      # 32 tokens per row at most
+    first_long = int(np.argmax(sess.prefix_lens > 32))
+    assert run(narrow) == first_long
+    neg = sess.prefix_lens.copy(); neg[0] = -5
+    assert run(good, torch.from_numpy(neg).to(DEV)) == 0
+    bad = good.copy(); bad[2, 4] = 10 ** 6                          # beyond the session's blocks: ignored
+    assert run(bad) == -1
