@@ -102,3 +102,11 @@ def test_host_validation_rejects_without_launching():
     assert lib.symph_mfma_reference(0, None, 0x10, None) == EINVAL
     assert lib.symph_mfma_reference(8, None, None, None) == EINVAL
     assert S.status_string(0) == "ok" and "unsupported" in S.status_string(-2)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
