@@ -538,6 +538,16 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     copy_ms = e0.elapsed_time(e1) / 5
+    # the runtime's own device-to-device copy of the same bytes (torch's copy_ of contiguous tensors is hipMemcpyAsync)
+    for _ in range(2):
+        scratch.copy_(buf)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        scratch.copy_(buf)
+    e1.record()
+    torch.cuda.synchronize()
+    memcpy_ms = e0.elapsed_time(e1) / 5
     del scratch
 
     # ---- append of the turn's K,V rows to the cache (one layer): small, outside the step, reported on its own ------
@@ -695,7 +705,8 @@ def main():
                                 "pct_mfma_bf16_peak": 100 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                                 "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops,
                                 **spread["prefix_prefill_attn"]},
-        "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6},
+        "contiguous_copy": {"ms": copy_ms, "GBps": mig_bytes / copy_ms / 1e6,
+                            "runtime_memcpy_d2d_ms": memcpy_ms, "runtime_memcpy_d2d_GBps": mig_bytes / memcpy_ms / 1e6},
         "kv_append_one_layer": {"us": append_us, "GBps": append_bytes / append_us / 1e3, "bytes": append_bytes},
         "kv_pack_tail_new_turn": {"ms": tail_ms, "GBps": 2.0 * tail_payload / tail_ms / 1e6, "payload_bytes": tail_payload,
                                   "pct_hbm_peak": 100 * 2.0 * tail_payload / tail_ms / 1e6 / HBM_PEAK_GBS},
