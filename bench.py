@@ -697,10 +697,10 @@ def main():
                    "n_kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "block_size": bs, "pool_blocks": nb,
                    "prefix_tokens": total, "new_tokens": sess.total_new_tokens, "payload_bytes": payload,
                    "step": "kv_pack(all layers) + kv_unpack(all layers) + prefix_prefill_attn(one layer)"},
-        "kv_pack": {"ms": pack_ms, "GBps": pack_gbs, "pct_hbm_peak": 100 * pack_gbs / HBM_PEAK_GBS,
+        "kv_pack": {"ms": pack_ms, "GBps": pack_gbs, "payload_GBps": pack_gbs / 2, "pct_hbm_peak": 100 * pack_gbs / HBM_PEAK_GBS,
                     **spread["kv_pack"]},
-        "kv_unpack": {"ms": unpack_ms, "GBps": unpack_gbs, "pct_hbm_peak": 100 * unpack_gbs / HBM_PEAK_GBS,
-                      **spread["kv_unpack"]},
+        "kv_unpack": {"ms": unpack_ms, "GBps": unpack_gbs, "payload_GBps": unpack_gbs / 2,
+                      "pct_hbm_peak": 100 * unpack_gbs / HBM_PEAK_GBS, **spread["kv_unpack"]},
         "prefix_prefill_attn": {"ms": attn_ms, "TFLOPs": attn_tflops,
                                 "pct_mfma_bf16_peak": 100 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                                 "kv_GBps": attn_bytes / attn_ms / 1e6, "flops": attn_flops,
