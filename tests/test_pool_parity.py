@@ -175,3 +175,27 @@ def test_argument_checks_change_nothing():
     got = pool.settle()
     assert sorted(x[:3] for x in got) == [(0, 1, 1), (1, 7, 0), (1, 7, 1)]
     assert pool.resident_layers(1) == 1 and pool.resident_layers(7) == 2 and pool.counts() == (1, 5, 2)
+
+
+def test_extreme_lengths_and_many_sessions():
+    """A session larger than the pool is never admitted (and overflows nothing); ten thousand sessions competing for
+    a pool that holds part of their first layer agree with the oracle."""
+    pool = S.KvPool(80, 100000, 16)
+    sessions = {1: 2 ** 31 - 1, 2: 1, -9: 16000}
+    for sid, n in sessions.items():
+        pool.advise(sid, n)
+    pool.settle()
+    want = PR.resident_layers(sessions, 80, 16, 100000)
+    assert {sid: pool.resident_layers(sid) for sid in sessions} == want == {1: 0, 2: 80, -9: 80}
+    pool.close()
+    rng = np.random.default_rng(0)
+    lens = {i: int(n) for i, n in enumerate(rng.integers(1, 9000, size=10000))}
+    big = S.KvPool(32, 2_000_000, 16)
+    for sid, n in lens.items():
+        big.advise(sid, n)
+    big.settle()
+    want = PR.resident_layers(lens, 32, 16, 2_000_000)
+    assert all(big.resident_layers(sid) == want[sid] for sid in lens)
+    free, lent, fw = big.counts()
+    assert fw == 0 and lent == sum(want[s] * PR.blocks_of(lens[s], 16) for s in lens) and free == 2_000_000 - lent
+    big.close()
