@@ -1342,6 +1342,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
     const int slot = (m.n_chunks > 0 || ch == 0) ? m.pslot0 + ch : p.dec_pslot_base + 2 * (first_wg + ch);
     return p.partials + ((int64_t)slot * Hkv + kvh) * kPartialFloats + tid;
   };
+  // Rows past the session's new tokens hold nothing (a one-token turn fills 4 of a slot's 128 rows): their lanes, in
+  // pairs l and l ^ 32 (the two halves of one row), read no partial results.  No barrier follows.
+  if (tok >= N) return;
   float M = -INFINITY;
   for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, chunk(ch)[64 * 256]);
   float acc[16];
