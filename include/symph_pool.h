@@ -80,6 +80,9 @@ int32_t symph_pool_settle(symph_pool* pool, symph_pool_change* h_changes, int32_
 /* Resident layers of an announced session (0 .. n_layers), or SYMPH_EINVAL if it is not known. */
 int32_t symph_pool_resident_layers(const symph_pool* pool, int64_t session);
 
+/* Slots per layer of an announced session, ceil(n_tokens / block_size), or SYMPH_EINVAL if it is not known. */
+int32_t symph_pool_unit_slots(const symph_pool* pool, int64_t session);
+
 /* The slots of one resident unit (its block table), h_slots [max_slots]; returns their number, SYMPH_EINVAL if the
  * unit is not resident, SYMPH_EWORKSPACE if max_slots is too small. */
 int32_t symph_pool_table(const symph_pool* pool, int64_t session, int32_t layer, int32_t* h_slots, int32_t max_slots);

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     # symph_pool.h (host code only)
     "symph_pool_create", "symph_pool_destroy", "symph_pool_advise", "symph_pool_drop", "symph_pool_claim",
     "symph_pool_framework_take", "symph_pool_framework_give", "symph_pool_settle", "symph_pool_resident_layers",
-    "symph_pool_table", "symph_pool_counts",
+    "symph_pool_unit_slots", "symph_pool_table", "symph_pool_counts",
 )
 
 
@@ -113,6 +113,8 @@ def load_library():
     lib.symph_pool_settle.argtypes = [vp, C.POINTER(_PoolChange), i32, ip, i32, ip, ip]
     lib.symph_pool_resident_layers.restype = i32
     lib.symph_pool_resident_layers.argtypes = [vp, i64]
+    lib.symph_pool_unit_slots.restype = i32
+    lib.symph_pool_unit_slots.argtypes = [vp, i64]
     lib.symph_pool_table.restype = i32
     lib.symph_pool_table.argtypes = [vp, i64, i32, ip, i32]
     lib.symph_pool_counts.restype = i32
@@ -398,23 +400,23 @@ class KvPool:
         self._check(self._lib.symph_pool_counts(self._h, C.byref(f), C.byref(l), C.byref(w)), "symph_pool_counts")
         return f.value, l.value, w.value
 
+    def unit_slots(self, session: int) -> int:
+        """Slots one layer of the session takes."""
+        return self._check(self._lib.symph_pool_unit_slots(self._h, session), "symph_pool_unit_slots")
+
     def table(self, session: int, layer: int) -> list[int]:
-        cap = self.n_slots
-        buf = (C.c_int32 * cap)()
+        cap = self.unit_slots(session)
+        buf = (C.c_int32 * max(cap, 1))()
         n = self._check(self._lib.symph_pool_table(self._h, session, layer, buf, cap), "symph_pool_table")
         return list(buf[:n])
 
     def claim(self, session: int) -> list[list[int]]:
         """Tables of the resident layers, which now belong to the framework."""
-        cap = self.n_slots
-        buf = (C.c_int32 * cap)()
+        b = self.unit_slots(session)
+        cap = b * self.resident_layers(session)
+        buf = (C.c_int32 * max(cap, 1))()
         r = C.c_int32()
-        lent_before = self.counts()[1]
         self._check(self._lib.symph_pool_claim(self._h, session, buf, cap, C.byref(r)), "symph_pool_claim")
-        if r.value == 0:
-            return []
-        n = lent_before - self.counts()[1]          # r tables of equal length, back to back
-        b = n // r.value
         return [list(buf[i * b:(i + 1) * b]) for i in range(r.value)]
 
     def framework_take(self, n: int) -> list[int]:

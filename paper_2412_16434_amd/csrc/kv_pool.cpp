@@ -328,6 +328,12 @@ int32_t symph_pool_resident_layers(const symph_pool* pool, int64_t session) {
   return it == pool->sessions.end() ? (int32_t)SYMPH_EINVAL : it->second.resident();
 }
 
+int32_t symph_pool_unit_slots(const symph_pool* pool, int64_t session) {
+  if (!pool) return SYMPH_EINVAL;
+  auto it = pool->sessions.find(session);
+  return it == pool->sessions.end() ? (int32_t)SYMPH_EINVAL : it->second.blocks;
+}
+
 int32_t symph_pool_table(const symph_pool* pool, int64_t session, int32_t layer, int32_t* h_slots, int32_t max_slots) {
   if (!pool || layer < 0) return SYMPH_EINVAL;
   auto it = pool->sessions.find(session);
