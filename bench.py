@@ -616,19 +616,18 @@ def main():
     for i, n in enumerate(pool_lens):
         kp.advise(i, int(n))
     import ctypes as C
-    from paper_2412_16434_amd.binding import _PoolChange
     lib, n_take = S.load_library(), pool_blocks // 16
-    changes = (_PoolChange * (512 * cfg.n_layers))()
+    changes = (S.PoolChange * (512 * cfg.n_layers))()
     slot_arr = (C.c_int32 * (pool_blocks // 4))()
     take_arr = (C.c_int32 * n_take)()
     nc, ns = C.c_int32(), C.c_int32()
     t0 = time.perf_counter()
-    rc0 = lib.symph_pool_settle(kp._h, changes, len(changes), slot_arr, len(slot_arr), C.byref(nc), C.byref(ns))
+    rc0 = lib.symph_pool_settle(kp.handle, changes, len(changes), slot_arr, len(slot_arr), C.byref(nc), C.byref(ns))
     t1 = time.perf_counter()
     loaded = nc.value
-    rc1 = lib.symph_pool_framework_take(kp._h, n_take, take_arr)
+    rc1 = lib.symph_pool_framework_take(kp.handle, n_take, take_arr)
     t2 = time.perf_counter()
-    rc2 = lib.symph_pool_settle(kp._h, changes, len(changes), slot_arr, len(slot_arr), C.byref(nc), C.byref(ns))
+    rc2 = lib.symph_pool_settle(kp.handle, changes, len(changes), slot_arr, len(slot_arr), C.byref(nc), C.byref(ns))
     t3 = time.perf_counter()
     assert rc0 == rc1 == rc2 == 0
     pool_stats = {"sessions": 512, "layers": cfg.n_layers, "slots": pool_blocks // 4,

@@ -7,6 +7,7 @@ is loaded on first use and a missing library is an error, never a fallback.
 from .binding import (  # noqa: F401
     KVCache,
     KvPool,
+    PoolChange,
     SymphError,
     lib_path,
     load_library,

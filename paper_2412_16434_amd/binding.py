@@ -44,6 +44,9 @@ class _PoolChange(C.Structure):
                 ("slot_begin", C.c_int32)]
 
 
+PoolChange = _PoolChange
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -369,6 +372,12 @@ class KvPool:
         st = self._lib.symph_pool_create(n_layers, n_slots, block_size, C.byref(self._h))
         if st != 0:
             raise SymphError(st, "symph_pool_create")
+
+    @property
+    def handle(self):
+        """The symph_pool* as a ctypes void pointer, for callers that drive the C entry points with arrays of their own
+        (``PoolChange`` is the change record)."""
+        return self._h
 
     def close(self):
         if self._h:

@@ -169,7 +169,7 @@ def test_argument_checks_change_nothing():
     # settle with arrays that are too small reports the need and changes nothing
     pool.advise(7, 16)
     nc, ns = C.c_int32(), C.c_int32()
-    assert lib.symph_pool_settle(pool._h, None, 0, None, 0, C.byref(nc), C.byref(ns)) == -4
+    assert lib.symph_pool_settle(pool.handle, None, 0, None, 0, C.byref(nc), C.byref(ns)) == -4
     assert (nc.value, ns.value) == (3, 2) and pool.resident_layers(7) == 0 and pool.resident_layers(1) == 2
     # capacity 6: layer 0 of session 1 (3), layer 0 of session 7 (1), layer 1: session 1 does not fit in 2, session 7 does
     got = pool.settle()
