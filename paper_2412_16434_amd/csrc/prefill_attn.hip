@@ -1547,12 +1547,12 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
     p.table = a.table ? a.table + (int64_t)s0 * a.table_stride : nullptr;
     p.n_sessions = ns;
     hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
-    if (!dec_mode) {  // (with the decode kernel on, every session is a short turn and the work list is empty)
-      if (a.block_size == 16)
-        hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
-      else
-        hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
-    }
+    // (Launched for decode-only batches too, where its work list is empty if max_new_len was a true bound: a session
+    // longer than the caller stated is then still computed, by this kernel, instead of being dropped.)
+    if (a.block_size == 16)
+      hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
     if (g_dec > 0) {
       if (a.block_size == 16)
         hipLaunchKernelGGL((attn_decode_kernel<G, 4>), dim3((unsigned)g_dec), dim3(256), 0, stream, p);
