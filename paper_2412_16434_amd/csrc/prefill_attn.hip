@@ -251,6 +251,17 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
       dec_total += tot_t;
     }
     if (tid == 0) p.dec_off[n_dec] = dec_total;
+    if (U == n_dec) {  // every unit is a short turn (each has exactly one): nothing for the work list
+      if (tid == 0) {
+        p.hdr[0] = 0;
+        p.hdr[1] = 0;
+        p.hdr[2] = 0;
+        p.hdr[3] = 0;
+        p.hdr[4] = n_dec;
+        p.hdr[5] = dec_total;
+      }
+      return;
+    }
   }
   __syncthreads();
   // unit u -> (session, first token, prefix length, new length)
