@@ -190,23 +190,23 @@ def decode_step(args):
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     kv_bytes = float(prefix_h.sum() + n) * 2 * cfg.n_kv_heads * cfg.head_dim * 2
 
-    def timed():
+    def timed(tuning):
+        call = lambda: S.prefix_prefill_attn(cache, 0, q, k_new, v_new, out, cu, prefix, table, 1, max_prefix, cfg.scale,
+                                             workspace=ws, tuning=tuning)
         for _ in range(max(args.warmup, 2)):
-            S.prefix_prefill_attn(cache, 0, q, k_new, v_new, out, cu, prefix, table, 1, max_prefix, cfg.scale, workspace=ws)
+            call()
         ts = []
         for _ in range(args.steps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            S.prefix_prefill_attn(cache, 0, q, k_new, v_new, out, cu, prefix, table, 1, max_prefix, cfg.scale, workspace=ws)
+            call()
             e1.record()
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
         return float(np.median(ts)), out.clone()
 
-    dec_ms, dec_out = timed()
-    os.environ["SYMPH_ATTN_DECODE"] = "0"
-    main_ms, main_out = timed()
-    del os.environ["SYMPH_ATTN_DECODE"]
+    dec_ms, dec_out = timed(None)
+    main_ms, main_out = timed(S.AttnTuning(decode=-1))   # (needs no more workspace than the default plan)
     diff = float((dec_out.float() - main_out.float()).abs().max())
     gbs = kv_bytes / dec_ms / 1e6
     print(json.dumps({

@@ -10,14 +10,15 @@
  * Conventions for every entry point
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers; everything else is passed by value.
  *   - The caller owns every buffer.  The library allocates no memory (symph_debug_check_tables aside) and keeps no
- *     state between calls; calls may be issued concurrently on different streams as long as the memory they write
- *     does not overlap.
+ *     state between calls (it reads no environment variable either: what can be tuned is an explicit argument);
+ *     calls may be issued concurrently on different streams as long as the memory they write does not overlap.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work and return
  *     without synchronising; device arrays must stay valid until the stream has executed the work.
  *   - Return value: SYMPH_OK or a negative symph_status.  Nothing aborts or throws across the ABI.  Host-visible
  *     arguments are validated before anything is launched.  Contents of device arrays (block ids, lengths) are
- *     the caller's contract; kernels additionally skip any block id outside [0, n_blocks) and any token beyond
- *     the buffer instead of touching memory out of range.
+ *     the caller's contract; kernels additionally never touch memory through a block id outside [0, n_blocks) or for
+ *     a token beyond the buffer: pack / unpack / append skip such rows, attention reads a row of zeros for them (the
+ *     key then has score 0 and value 0 in every kernel of the attention path).
  *
  * Layouts ("element" = one value of cache dtype: bf16 = 2 bytes, fp32 = 4 bytes)
  *   paged cache   K pool and V pool.  Element (layer l, block b, slot o, kv-head g, dim c) of K lives at
@@ -156,13 +157,20 @@ int32_t symph_kv_append(const symph_kv_cache* cache, int32_t layer, const void* 
  * The new turn's K,V are NOT yet in the paged cache; they are passed as k_new / v_new.
  *   layer: which layer of `cache` holds the prefix.  q/k_new/v_new/out have the cache dtype.
  *   d_cu_new_lens [n_sessions+1] int32, d_prefix_lens [n_sessions] int32, d_block_table as above.
- *   total_new_tokens = T, max_new_len >= max N_s, max_prefix_len >= max P_s (host copies, to size grids).
+ *   total_new_tokens = T, max_new_len >= max N_s, max_prefix_len >= max P_s (host copies).  total_new_tokens and
+ *   n_sessions size the grids and the work list; max_prefix_len is only checked against the table width; max_new_len
+ *   only chooses kernels: a batch with max_new_len * (n_q_heads / n_kv_heads) <= 32 is a decode step and its short
+ *   turns run in a kernel that splits the keys among waves.  Neither of the two is relied on for memory safety: a
+ *   session longer than stated is still computed, and computed correctly (a turn with more new tokens than stated is
+ *   not a short turn for the device-side scheduler and goes through the general kernel), only not at the best speed.
  *   scale > 0 and finite (fp32).  d_workspace: device scratch of at least
  *   symph_prefix_prefill_attn_workspace_bytes(...) bytes, 256-byte aligned (may be NULL when that is 0).
  * Arithmetic: bf16 inputs, fp32 accumulation on MFMA, fp32 online softmax, probabilities rounded to bf16 before
  * the P*V product, output rounded to nearest even; fp32 inputs are computed in fp32 throughout.
  * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads.  Sessions with N_s == 0 produce no rows;
- * P_s == 0 is a plain causal prefill.
+ * P_s == 0 is a plain causal prefill.  The matrix-core kernels cover bf16, head_dim 128, group sizes 1, 2, 4, 8, 16 and
+ * block sizes that are powers of two >= 16; every other supported shape (fp32, head_dim 64, other group sizes, smaller
+ * blocks) runs a plain kernel with one wave per query row: correct, not tuned, and its workspace query returns 0.
  */
 int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
                                   const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
@@ -171,10 +179,52 @@ int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, co
                                   int32_t max_new_len, int32_t max_prefix_len, float scale, void* d_workspace,
                                   int64_t workspace_bytes, void* stream);
 
-/* Scratch bytes symph_prefix_prefill_attn needs for these host-side bounds (0 is possible). Negative on bad input. */
+/* Scratch bytes symph_prefix_prefill_attn needs for these host-side bounds (the same values as in the call; 0 is
+ * possible).  Negative on bad input. */
 int64_t symph_prefix_prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
                                                   int32_t total_new_tokens, int32_t max_new_len,
                                                   int32_t max_prefix_len);
+
+/*
+ * How the attention call cuts a ragged batch into workgroup-sized pieces (Sec. 2.2: prefill is compute-bound, decode
+ * memory-bound, and one batch mixes both).  A field that is 0 keeps its default, so a zeroed struct, or a null
+ * pointer, is the default behaviour; the values do not change what is computed, only how the work is divided.
+ */
+typedef struct {
+  int32_t slots;       /* workgroups resident on the GPU at once, which the work list is balanced for (default 512) */
+  int32_t c_min;       /* shortest piece of a (session, query tile) unit that is split, in 64-key tiles (default 8) */
+  int32_t coarse;      /* > 0 (default): with at least two units per slot only the longest units are split; < 0: every
+                          unit is cut so that there are about two pieces per slot */
+  int32_t decode;      /* > 0 (default): decode steps (see max_new_len above) take the key-splitting kernel; < 0: never */
+  int32_t decode_wgs;  /* workgroups of that kernel, summed over the kv-heads (default 512) */
+  int32_t reserved[3]; /* 0 */
+} symph_attn_tuning;
+
+/* The same two calls with explicit tuning values.  The workspace query and the call must be given the same values: a
+ * call whose workspace is smaller than its own values require returns SYMPH_EWORKSPACE. */
+int32_t symph_prefix_prefill_attn_tuned(const symph_kv_cache* cache, int32_t layer, const void* d_q,
+                                        const void* d_k_new, const void* d_v_new, void* d_out,
+                                        const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens,
+                                        const int32_t* d_block_table, int32_t table_stride, int32_t n_sessions,
+                                        int32_t n_q_heads, int32_t total_new_tokens, int32_t max_new_len,
+                                        int32_t max_prefix_len, float scale, void* d_workspace,
+                                        int64_t workspace_bytes, void* stream, const symph_attn_tuning* tuning);
+int64_t symph_prefix_prefill_attn_workspace_bytes_tuned(const symph_kv_cache* cache, int32_t n_sessions,
+                                                        int32_t n_q_heads, int32_t total_new_tokens,
+                                                        int32_t max_new_len, int32_t max_prefix_len,
+                                                        const symph_attn_tuning* tuning);
+
+/*
+ * What the device-side scheduler of the last attention call on `d_workspace` reported (a debugging aid like
+ * symph_debug_check_tables: it copies one word to the host and synchronises `stream`).  *h_flags: bit 0 - a unit that
+ * should have been split was left whole because the workspace has no room for its pieces (slower, still correct; it
+ * cannot happen with a workspace of the queried size); bit 1 - the lengths on the device describe more query tiles
+ * than total_new_tokens and n_sessions allow, and the work beyond that bound was NOT done (the caller broke the
+ * contract on d_cu_new_lens).  0 for shapes that need no workspace.
+ */
+#define SYMPH_ATTN_FLAG_UNSPLIT 1
+#define SYMPH_ATTN_FLAG_DROPPED 2
+int32_t symph_debug_attn_flags(const void* d_workspace, void* stream, int32_t* h_flags);
 
 /*
  * Host staging on a side stream (Sec. 2.4 "Swap": K,V swapped to host memory; Sec. 3.3: asynchronous reads and

@@ -5,6 +5,7 @@ every step of the path runs in the HIP kernels.  Importing this package does not
 is loaded on first use and a missing library is an error, never a fallback.
 """
 from .binding import (  # noqa: F401
+    AttnTuning,
     KVCache,
     KvPool,
     PoolChange,
@@ -30,6 +31,7 @@ from .binding import (  # noqa: F401
     device_copy,
     mfma_reference,
     debug_check_tables,
+    debug_attn_flags,
     status_string,
     EXPORTED_SYMBOLS,
 )

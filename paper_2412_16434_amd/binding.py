@@ -16,7 +16,8 @@ SYMPH_BF16, SYMPH_FP32 = 0, 1
 EXPORTED_SYMBOLS = (
     "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
     "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_pack_units", "symph_kv_unpack_units", "symph_kv_append",
-    "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_stage_to_host",
+    "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_prefix_prefill_attn_tuned",
+    "symph_prefix_prefill_attn_workspace_bytes_tuned", "symph_debug_attn_flags", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
     "symph_mfma_reference", "symph_debug_check_tables",
     "symph_status_string",
@@ -37,6 +38,12 @@ class _CacheStruct(C.Structure):
     _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("layer_stride", C.c_int64),
                 ("block_stride", C.c_int64), ("n_layers", C.c_int32), ("n_blocks", C.c_int32),
                 ("block_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+
+
+class AttnTuning(C.Structure):
+    """symph_attn_tuning: a field left 0 keeps the library's default."""
+    _fields_ = [("slots", C.c_int32), ("c_min", C.c_int32), ("coarse", C.c_int32), ("decode", C.c_int32),
+                ("decode_wgs", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 class _PoolChange(C.Structure):
@@ -86,6 +93,13 @@ def load_library():
                                               vp, i64, vp]
     lib.symph_prefix_prefill_attn_workspace_bytes.restype = i64
     lib.symph_prefix_prefill_attn_workspace_bytes.argtypes = [cp, i32, i32, i32, i32, i32]
+    tp = C.POINTER(AttnTuning)
+    lib.symph_prefix_prefill_attn_tuned.restype = i32
+    lib.symph_prefix_prefill_attn_tuned.argtypes = lib.symph_prefix_prefill_attn.argtypes + [tp]
+    lib.symph_prefix_prefill_attn_workspace_bytes_tuned.restype = i64
+    lib.symph_prefix_prefill_attn_workspace_bytes_tuned.argtypes = [cp, i32, i32, i32, i32, i32, tp]
+    lib.symph_debug_attn_flags.restype = i32
+    lib.symph_debug_attn_flags.argtypes = [vp, vp, C.POINTER(i32)]
     for fn in (lib.symph_stage_to_host, lib.symph_stage_to_device):
         fn.restype = i32
         fn.argtypes = [vp, vp, i64, vp, vp, vp]
@@ -161,6 +175,42 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+def _dev(t, name: str, dtype=None, allow_none: bool = False, pinned_ok: bool = False):
+    """Check what the C side cannot see: the tensor is on the GPU (or, for buffers, pinned host memory), contiguous and
+    of the element type the entry point reads it as.  Returns its data pointer."""
+    if t is None:
+        if allow_none:
+            return None
+        raise ValueError(f"{name} is required")
+    if not (t.is_cuda or (pinned_ok and t.is_pinned())):
+        raise ValueError(f"{name} must be a device tensor" + (" or pinned host memory" if pinned_ok else ""))
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, not {t.dtype}")
+    return t.data_ptr()
+
+
+def _table(t, name: str = "block_table"):
+    """(pointer, row stride in entries) of an int32 [n_sessions][stride] block table on the device; (None, 0) if absent."""
+    import torch
+    if t is None:
+        return None, 0
+    if t.dim() != 2:
+        raise ValueError(f"{name} must be a 2-D int32 tensor [n_sessions][max_blocks]")
+    return _dev(t, name, torch.int32), t.shape[1]
+
+
+def _lens(t, name: str):
+    import torch
+    return _dev(t, name, torch.int32)
+
+
+def _offsets(t, name: str):
+    import torch
+    return _dev(t, name, torch.int64)
+
+
 def _stream_ptr(stream) -> Optional[int]:
     if stream is None:
         import torch
@@ -192,52 +242,49 @@ def kv_buffer_bytes(cache: KVCache, total_tokens: int) -> int:
     return int(n)
 
 
+def _migrate(fn_name: str, cache: KVCache, head_args, block_table, prefix_lens, mid, offsets, total_tokens, buf, stream):
+    """Shared marshalling of the pack / unpack family: (cache, [layer range], table, stride, lens, [extra], offsets, n,
+    total, buf, bytes, stream)."""
+    st = cache.struct()
+    tp, stride = _table(block_table)
+    _check(getattr(load_library(), fn_name)(
+        C.byref(st), *head_args, tp, stride, _lens(prefix_lens, "prefix_lens"), *mid, _offsets(offsets, "offsets"),
+        prefix_lens.shape[0], int(total_tokens), _dev(buf, "buf", pinned_ok=True), buf.numel() * buf.element_size(),
+        _stream_ptr(stream)), fn_name)
+
+
 def kv_pack(cache: KVCache, block_table, prefix_lens, buf_token_offsets, total_tokens: int, buf, stream=None) -> None:
     """Gather into ``buf`` (any dtype, 1-D device tensor of at least kv_buffer_bytes bytes)."""
-    st = cache.struct()
-    _check(load_library().symph_kv_pack(C.byref(st), _ptr(block_table), block_table.shape[1] if block_table.dim() == 2
-                                        else 0, _ptr(prefix_lens), _ptr(buf_token_offsets), prefix_lens.shape[0],
-                                        int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(),
-                                        _stream_ptr(stream)), "symph_kv_pack")
+    _migrate("symph_kv_pack", cache, (), block_table, prefix_lens, (), buf_token_offsets, total_tokens, buf, stream)
 
 
 def kv_unpack(cache: KVCache, dst_block_table, prefix_lens, buf_token_offsets, total_tokens: int, buf,
               stream=None) -> None:
-    st = cache.struct()
-    _check(load_library().symph_kv_unpack(C.byref(st), _ptr(dst_block_table), dst_block_table.shape[1]
-                                          if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens),
-                                          _ptr(buf_token_offsets), prefix_lens.shape[0], int(total_tokens), _ptr(buf),
-                                          buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_unpack")
+    _migrate("symph_kv_unpack", cache, (), dst_block_table, prefix_lens, (), buf_token_offsets, total_tokens, buf,
+             stream)
 
 
 def kv_pack_layers(cache: KVCache, layer_begin: int, layer_end: int, block_table, prefix_lens, buf_token_offsets,
                    total_tokens: int, buf, stream=None) -> None:
     """Gather layers ``layer_begin .. layer_end-1`` only into ``buf`` (whole-cache layout)."""
-    st = cache.struct()
-    _check(load_library().symph_kv_pack_layers(
-        C.byref(st), int(layer_begin), int(layer_end), _ptr(block_table),
-        block_table.shape[1] if block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
-        prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
-        "symph_kv_pack_layers")
+    _migrate("symph_kv_pack_layers", cache, (int(layer_begin), int(layer_end)), block_table, prefix_lens, (),
+             buf_token_offsets, total_tokens, buf, stream)
 
 
 def kv_unpack_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block_table, prefix_lens,
                      buf_token_offsets, total_tokens: int, buf, stream=None) -> None:
-    st = cache.struct()
-    _check(load_library().symph_kv_unpack_layers(
-        C.byref(st), int(layer_begin), int(layer_end), _ptr(dst_block_table),
-        dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0, _ptr(prefix_lens), _ptr(buf_token_offsets),
-        prefix_lens.shape[0], int(total_tokens), _ptr(buf), buf.numel() * buf.element_size(), _stream_ptr(stream)),
-        "symph_kv_unpack_layers")
+    _migrate("symph_kv_unpack_layers", cache, (int(layer_begin), int(layer_end)), dst_block_table, prefix_lens, (),
+             buf_token_offsets, total_tokens, buf, stream)
 
 
 def _units(fn_name, slots: KVCache, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens, buf,
            stream):
     st = slots.struct()
+    tp, stride = _table(unit_table, "unit_table")
     _check(getattr(load_library(), fn_name)(
-        C.byref(st), _ptr(unit_table), unit_table.shape[1] if unit_table.dim() == 2 else 0, _ptr(unit_lens),
-        _ptr(unit_token_offsets), _ptr(unit_chunk_rows), unit_lens.shape[0], int(total_unit_tokens), _ptr(buf),
-        buf.numel() * buf.element_size(), _stream_ptr(stream)), fn_name)
+        C.byref(st), tp, stride, _lens(unit_lens, "unit_lens"), _offsets(unit_token_offsets, "unit_token_offsets"),
+        _offsets(unit_chunk_rows, "unit_chunk_rows"), unit_lens.shape[0], int(total_unit_tokens),
+        _dev(buf, "buf", pinned_ok=True), buf.numel() * buf.element_size(), _stream_ptr(stream)), fn_name)
 
 
 def kv_pack_units(slots: KVCache, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens: int,
@@ -257,9 +304,10 @@ def debug_check_tables(cache: KVCache, block_table, lens, is_destination: bool, 
     """-1 if the table and lengths keep the contract the kernels rely on, else the first offending session."""
     st = cache.struct()
     bad = C.c_int32(-1)
+    tp, stride = _table(block_table)
     rc = load_library().symph_debug_check_tables(
-        C.byref(st), _ptr(block_table), block_table.shape[1] if block_table.dim() == 2 else 0, _ptr(lens),
-        lens.shape[0], 1 if is_destination else 0, _stream_ptr(stream), C.byref(bad))
+        C.byref(st), tp, stride, _lens(lens, "lens"), lens.shape[0], 1 if is_destination else 0, _stream_ptr(stream),
+        C.byref(bad))
     if rc != 0 and bad.value < 0:
         _check(rc, "symph_debug_check_tables")
     return bad.value
@@ -268,52 +316,82 @@ def debug_check_tables(cache: KVCache, block_table, lens, is_destination: bool, 
 def kv_pack_tail(cache: KVCache, block_table, prefix_lens, tail_begin, tail_offsets, total_tail_tokens: int, buf,
                  stream=None) -> None:
     """Gather tokens ``tail_begin[s] .. prefix_lens[s]-1`` of every session (all layers) into ``buf``."""
-    st = cache.struct()
-    _check(load_library().symph_kv_pack_tail(
-        C.byref(st), _ptr(block_table), block_table.shape[1] if block_table.dim() == 2 else 0, _ptr(prefix_lens),
-        _ptr(tail_begin), _ptr(tail_offsets), prefix_lens.shape[0], int(total_tail_tokens), _ptr(buf),
-        buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_pack_tail")
+    _migrate("symph_kv_pack_tail", cache, (), block_table, prefix_lens, (_lens(tail_begin, "tail_begin"),),
+             tail_offsets, total_tail_tokens, buf, stream)
 
 
 def kv_unpack_tail(cache: KVCache, dst_block_table, prefix_lens, tail_begin, tail_offsets, total_tail_tokens: int, buf,
                    stream=None) -> None:
     """Scatter a tail buffer (see ``kv_pack_tail``) into the cache through ``dst_block_table``."""
-    st = cache.struct()
-    _check(load_library().symph_kv_unpack_tail(
-        C.byref(st), _ptr(dst_block_table), dst_block_table.shape[1] if dst_block_table.dim() == 2 else 0,
-        _ptr(prefix_lens), _ptr(tail_begin), _ptr(tail_offsets), prefix_lens.shape[0], int(total_tail_tokens), _ptr(buf),
-        buf.numel() * buf.element_size(), _stream_ptr(stream)), "symph_kv_unpack_tail")
+    _migrate("symph_kv_unpack_tail", cache, (), dst_block_table, prefix_lens, (_lens(tail_begin, "tail_begin"),),
+             tail_offsets, total_tail_tokens, buf, stream)
 
 
 def kv_append(cache: KVCache, layer: int, k_new, v_new, cu_new_lens, prefix_lens, block_table, stream=None) -> None:
     """Write the new turn's K,V rows of ``layer`` into the paged cache behind each session's prefix."""
     st = cache.struct()
+    dt = cache.k_pool.dtype
+    tp, stride = _table(block_table)
     _check(load_library().symph_kv_append(
-        C.byref(st), int(layer), _ptr(k_new), _ptr(v_new), _ptr(cu_new_lens), _ptr(prefix_lens), _ptr(block_table),
-        block_table.shape[1] if block_table.dim() == 2 else 0, prefix_lens.shape[0], k_new.shape[0],
-        _stream_ptr(stream)), "symph_kv_append")
+        C.byref(st), int(layer), _dev(k_new, "k_new", dt), _dev(v_new, "v_new", dt), _lens(cu_new_lens, "cu_new_lens"),
+        _lens(prefix_lens, "prefix_lens"), tp, stride, prefix_lens.shape[0], k_new.shape[0], _stream_ptr(stream)),
+        "symph_kv_append")
+
+
+def _tuning_ref(tuning):
+    return None if tuning is None else C.byref(tuning)
 
 
 def prefix_prefill_attn_workspace_bytes(cache: KVCache, n_sessions: int, n_q_heads: int, total_new_tokens: int,
-                                        max_new_len: int, max_prefix_len: int) -> int:
+                                        max_new_len: int, max_prefix_len: int, tuning: Optional[AttnTuning] = None) -> int:
     st = cache.struct()
-    n = load_library().symph_prefix_prefill_attn_workspace_bytes(C.byref(st), n_sessions, n_q_heads, total_new_tokens,
-                                                                 max_new_len, max_prefix_len)
+    lib = load_library()
+    if tuning is None:
+        n = lib.symph_prefix_prefill_attn_workspace_bytes(C.byref(st), n_sessions, n_q_heads, total_new_tokens,
+                                                          max_new_len, max_prefix_len)
+    else:
+        n = lib.symph_prefix_prefill_attn_workspace_bytes_tuned(C.byref(st), n_sessions, n_q_heads, total_new_tokens,
+                                                                max_new_len, max_prefix_len, C.byref(tuning))
     if n < 0:
         raise SymphError(-1, "symph_prefix_prefill_attn_workspace_bytes")
     return int(n)
 
 
+def _attn_args(cache: KVCache, layer, q, k_new, v_new, out, cu_new_lens, prefix_lens, block_table, max_new_len,
+               max_prefix_len, scale):
+    """The argument list the attention entry points share, up to and including ``scale``."""
+    dt = cache.k_pool.dtype
+    if q.dim() != 3 or out.shape != q.shape or k_new.dim() != 3 or v_new.shape != k_new.shape:
+        raise ValueError("q / out must be [T][H_q][d] and k_new / v_new [T][H_kv][d]")
+    tp, stride = _table(block_table)
+    return [int(layer), _dev(q, "q", dt), _dev(k_new, "k_new", dt), _dev(v_new, "v_new", dt), _dev(out, "out", dt),
+            _lens(cu_new_lens, "cu_new_lens"), _lens(prefix_lens, "prefix_lens"), tp, stride, prefix_lens.shape[0],
+            q.shape[1], q.shape[0], int(max_new_len), int(max_prefix_len), float(scale)]
+
+
 def prefix_prefill_attn(cache: KVCache, layer: int, q, k_new, v_new, out, cu_new_lens, prefix_lens, block_table,
-                        max_new_len: int, max_prefix_len: int, scale: float, workspace=None, stream=None) -> None:
+                        max_new_len: int, max_prefix_len: int, scale: float, workspace=None, stream=None,
+                        tuning: Optional[AttnTuning] = None) -> None:
     """out[T][H_q][d] <- attention of the new turn over [cached prefix ; causal new tokens] for one layer."""
     st = cache.struct()
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load_library().symph_prefix_prefill_attn(
-        C.byref(st), int(layer), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(cu_new_lens), _ptr(prefix_lens),
-        _ptr(block_table), block_table.shape[1] if block_table is not None and block_table.dim() == 2 else 0,
-        prefix_lens.shape[0], q.shape[1], q.shape[0], int(max_new_len), int(max_prefix_len), float(scale),
-        _ptr(workspace), ws_bytes, _stream_ptr(stream)), "symph_prefix_prefill_attn")
+    args = _attn_args(cache, layer, q, k_new, v_new, out, cu_new_lens, prefix_lens, block_table, max_new_len,
+                      max_prefix_len, scale)
+    args += [_dev(workspace, "workspace", allow_none=True), ws_bytes, _stream_ptr(stream)]
+    lib = load_library()
+    if tuning is None:
+        _check(lib.symph_prefix_prefill_attn(C.byref(st), *args), "symph_prefix_prefill_attn")
+    else:
+        _check(lib.symph_prefix_prefill_attn_tuned(C.byref(st), *args, C.byref(tuning)),
+               "symph_prefix_prefill_attn_tuned")
+
+
+def debug_attn_flags(workspace, stream=None) -> int:
+    """Flags of the device-side scheduler of the last attention call on ``workspace`` (synchronises the stream)."""
+    flags = C.c_int32(0)
+    _check(load_library().symph_debug_attn_flags(_dev(workspace, "workspace", allow_none=True), _stream_ptr(stream),
+                                                 C.byref(flags)), "symph_debug_attn_flags")
+    return flags.value
 
 
 def stage_to_host(h_pinned, d_buf, nbytes: int, producer_stream, side_stream, event) -> None:

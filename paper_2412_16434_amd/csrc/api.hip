@@ -179,20 +179,34 @@ int32_t symph_kv_append(const symph_kv_cache* cache, int32_t layer, const void* 
                           n_sessions, total_new_tokens, (hipStream_t)stream);
 }
 
+int64_t symph_prefix_prefill_attn_workspace_bytes_tuned(const symph_kv_cache* cache, int32_t n_sessions,
+                                                        int32_t n_q_heads, int32_t total_new_tokens,
+                                                        int32_t max_new_len, int32_t max_prefix_len,
+                                                        const symph_attn_tuning* tuning) {
+  if (!cache || n_sessions < 0 || n_q_heads <= 0 || total_new_tokens < 0 || max_new_len < 0 || max_prefix_len < 0)
+    return -1;
+  if (cache->n_kv_heads <= 0) return -1;
+  return prefill_attn_workspace_bytes(cache, n_sessions, n_q_heads, total_new_tokens, max_new_len, max_prefix_len,
+                                      tuning);
+}
+
 int64_t symph_prefix_prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
                                                   int32_t total_new_tokens, int32_t max_new_len,
                                                   int32_t max_prefix_len) {
-  if (!cache || n_sessions < 0 || n_q_heads <= 0 || total_new_tokens < 0 || max_new_len < 0 || max_prefix_len < 0)
-    return -1;
-  return prefill_attn_workspace_bytes(cache, n_sessions, n_q_heads, total_new_tokens, max_new_len, max_prefix_len);
+  return symph_prefix_prefill_attn_workspace_bytes_tuned(cache, n_sessions, n_q_heads, total_new_tokens, max_new_len,
+                                                         max_prefix_len, nullptr);
 }
 
-int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
-                                  const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
-                                  const int32_t* d_prefix_lens, const int32_t* d_block_table, int32_t table_stride,
-                                  int32_t n_sessions, int32_t n_q_heads, int32_t total_new_tokens,
-                                  int32_t max_new_len, int32_t max_prefix_len, float scale, void* d_workspace,
-                                  int64_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace symph {
+// Validation and argument marshalling shared by the attention entry points.
+int32_t prefill_attn_entry(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
+                           const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
+                           const int32_t* d_prefix_lens, const int32_t* d_block_table, int32_t table_stride,
+                           int32_t n_sessions, int32_t n_q_heads, int32_t total_new_tokens, int32_t max_new_len,
+                           int32_t max_prefix_len, float scale, void* d_workspace, int64_t workspace_bytes,
+                           void* stream, const symph_attn_tuning* tuning, bool fit_workspace) {
   int32_t rc = validate_cache(cache);
   if (rc != SYMPH_OK) return rc;
   if (layer < 0 || layer >= cache->n_layers) return SYMPH_EINVAL;
@@ -207,9 +221,10 @@ int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, co
   if (max_prefix_len > 0 && (!d_block_table || table_stride == 0)) return SYMPH_EINVAL;
   if (max_prefix_len > 0 && (int64_t)table_stride * cache->block_size < max_prefix_len) return SYMPH_EINVAL;
   if (cache->head_dim != 64 && cache->head_dim != 128) return SYMPH_EUNSUPPORTED;
+  if (tuning && (tuning->slots < 0 || tuning->c_min < 0 || tuning->decode_wgs < 0)) return SYMPH_EINVAL;
   const int64_t need = prefill_attn_workspace_bytes(cache, n_sessions, n_q_heads, total_new_tokens, max_new_len,
-                                                    max_prefix_len);
-  if (need > 0 && (!d_workspace || workspace_bytes < need)) return SYMPH_EWORKSPACE;
+                                                    max_prefix_len, tuning);
+  if (need > 0 && !fit_workspace && (!d_workspace || workspace_bytes < need)) return SYMPH_EWORKSPACE;
 
   const int eb = elem_bytes_of(cache->dtype);
   AttnArgs a;
@@ -237,7 +252,47 @@ int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, co
   a.scale = scale;
   a.workspace = d_workspace;
   a.workspace_bytes = workspace_bytes;
+  a.tuning = tuning;
+  a.fit_workspace = fit_workspace;
   return launch_prefill_attn(a, (hipStream_t)stream);
+}
+}  // namespace symph
+
+extern "C" {
+
+int32_t symph_prefix_prefill_attn_tuned(const symph_kv_cache* cache, int32_t layer, const void* d_q,
+                                        const void* d_k_new, const void* d_v_new, void* d_out,
+                                        const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens,
+                                        const int32_t* d_block_table, int32_t table_stride, int32_t n_sessions,
+                                        int32_t n_q_heads, int32_t total_new_tokens, int32_t max_new_len,
+                                        int32_t max_prefix_len, float scale, void* d_workspace,
+                                        int64_t workspace_bytes, void* stream, const symph_attn_tuning* tuning) {
+  return prefill_attn_entry(cache, layer, d_q, d_k_new, d_v_new, d_out, d_cu_new_lens, d_prefix_lens, d_block_table,
+                            table_stride, n_sessions, n_q_heads, total_new_tokens, max_new_len, max_prefix_len, scale,
+                            d_workspace, workspace_bytes, stream, tuning, false);
+}
+
+int32_t symph_prefix_prefill_attn(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
+                                  const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
+                                  const int32_t* d_prefix_lens, const int32_t* d_block_table, int32_t table_stride,
+                                  int32_t n_sessions, int32_t n_q_heads, int32_t total_new_tokens,
+                                  int32_t max_new_len, int32_t max_prefix_len, float scale, void* d_workspace,
+                                  int64_t workspace_bytes, void* stream) {
+  return prefill_attn_entry(cache, layer, d_q, d_k_new, d_v_new, d_out, d_cu_new_lens, d_prefix_lens, d_block_table,
+                            table_stride, n_sessions, n_q_heads, total_new_tokens, max_new_len, max_prefix_len, scale,
+                            d_workspace, workspace_bytes, stream, nullptr, false);
+}
+
+int32_t symph_debug_attn_flags(const void* d_workspace, void* stream, int32_t* h_flags) {
+  if (!h_flags) return SYMPH_EINVAL;
+  *h_flags = 0;
+  if (!d_workspace) return SYMPH_OK;  // a shape without a workspace has no scheduler
+  int32_t hdr[kAttnHdrInts];
+  if (hipMemcpyAsync(hdr, d_workspace, sizeof(hdr), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess ||
+      hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
+    return SYMPH_ELAUNCH;
+  *h_flags = hdr[kAttnHdrFlags];
+  return SYMPH_OK;
 }
 
 int32_t symph_stage_to_host(void* h_pinned, const void* d_buf, int64_t bytes, void* producer_stream,

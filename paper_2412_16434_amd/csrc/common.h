@@ -52,9 +52,22 @@ struct AttnArgs {
   float scale;
   void* workspace;
   int64_t workspace_bytes;
+  const symph_attn_tuning* tuning;  // null: defaults
+  bool fit_workspace;               // the workspace has a fixed size: cut the work list so that it is enough
 };
 int32_t launch_prefill_attn(const AttnArgs& a, hipStream_t stream);
 int64_t prefill_attn_workspace_bytes(const symph_kv_cache* cache, int32_t n_sessions, int32_t n_q_heads,
-                                     int32_t total_new_tokens, int32_t max_new_len, int32_t max_prefix_len);
+                                     int32_t total_new_tokens, int32_t max_new_len, int32_t max_prefix_len,
+                                     const symph_attn_tuning* tuning);
+// Validation and argument marshalling shared by the attention entry points (defined with them).
+int32_t prefill_attn_entry(const symph_kv_cache* cache, int32_t layer, const void* d_q, const void* d_k_new,
+                           const void* d_v_new, void* d_out, const int32_t* d_cu_new_lens,
+                           const int32_t* d_prefix_lens, const int32_t* d_block_table, int32_t table_stride,
+                           int32_t n_sessions, int32_t n_q_heads, int32_t total_new_tokens, int32_t max_new_len,
+                           int32_t max_prefix_len, float scale, void* d_workspace, int64_t workspace_bytes,
+                           void* stream, const symph_attn_tuning* tuning, bool fit_workspace);
+// Number of ints at the start of the attention workspace that hold counts and flags, and the index of the flags.
+constexpr int kAttnHdrInts = 8;
+constexpr int kAttnHdrFlags = 7;
 
 }  // namespace symph

@@ -12,8 +12,6 @@
 //     blockIdx.y walks groups of planes.
 #include "common.h"
 
-#include <stdlib.h>
-
 namespace symph {
 
 struct MigrateParams {
@@ -134,32 +132,19 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   }
 }
 
-static int env_int(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
-
-template <typename VecT, bool PACK, int PLANES, int NT>
-static void launch_uniform(bool uniform, dim3 grid, const MigrateParams& p, hipStream_t stream) {
-  if (uniform)
-    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, NT, true>), grid, dim3(256), 0, stream, p);
-  else
-    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, NT, false>), grid, dim3(256), 0, stream, p);
-}
+// Non-temporal loads and stores (every byte is touched once): bit 0 loads, bit 1 stores.
+constexpr int kMigrateNT = 3;
 
 template <typename VecT, bool PACK, int PLANES>
-static void launch_nt(int nt, dim3 grid, const MigrateParams& p, hipStream_t stream) {
-  const bool uniform = p.row_shift >= 6 && env_int("SYMPH_MIGRATE_UNIFORM", 1) != 0;
-  switch (nt & 3) {
-    case 0: launch_uniform<VecT, PACK, PLANES, 0>(uniform, grid, p, stream); break;
-    case 1: launch_uniform<VecT, PACK, PLANES, 1>(uniform, grid, p, stream); break;
-    case 2: launch_uniform<VecT, PACK, PLANES, 2>(uniform, grid, p, stream); break;
-    default: launch_uniform<VecT, PACK, PLANES, 3>(uniform, grid, p, stream); break;
-  }
+static void launch_uniform(dim3 grid, const MigrateParams& p, hipStream_t stream) {
+  if (p.row_shift >= 6)  // a row is a whole number of waves: scalar session search and table read
+    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, kMigrateNT, true>), grid, dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, kMigrateNT, false>), grid, dim3(256), 0, stream, p);
 }
 
 template <typename VecT, bool PACK>
-static int32_t launch_planes(int planes, int nt, const MigrateParams& p_in, hipStream_t stream) {
+static int32_t launch_planes(int planes, const MigrateParams& p_in, hipStream_t stream) {
   const int64_t n_vec = p_in.total_tokens * p_in.vecs_per_row;
   const int64_t gx = ceil_div64(n_vec, 256);
   const int64_t gy = ceil_div64(p_in.plane_end - p_in.plane_begin, planes);
@@ -167,17 +152,11 @@ static int32_t launch_planes(int planes, int nt, const MigrateParams& p_in, hipS
   dim3 grid((unsigned)gx, (unsigned)gy);
   MigrateParams p = p_in;
   // measured on MI355X (config 2): the gather gains 2-3 % from the XCD-contiguous mapping, the scatter loses 7 %
-  p.xcd_chunk = env_int("SYMPH_MIGRATE_XCD", PACK ? 1 : 0) ? (int32_t)(gx / 8) : 0;
-  switch (planes) {
-    case 1: launch_nt<VecT, PACK, 1>(nt, grid, p, stream); break;
-    case 2: launch_nt<VecT, PACK, 2>(nt, grid, p, stream); break;
-    case 3: launch_nt<VecT, PACK, 3>(nt, grid, p, stream); break;
-    case 4: launch_nt<VecT, PACK, 4>(nt, grid, p, stream); break;
-    case 5: launch_nt<VecT, PACK, 5>(nt, grid, p, stream); break;
-    case 6: launch_nt<VecT, PACK, 6>(nt, grid, p, stream); break;
-    case 8: launch_nt<VecT, PACK, 8>(nt, grid, p, stream); break;
-    default: return SYMPH_EINVAL;
-  }
+  p.xcd_chunk = PACK ? (int32_t)(gx / 8) : 0;
+  if (planes == 1)
+    launch_uniform<VecT, PACK, 1>(grid, p, stream);
+  else
+    launch_uniform<VecT, PACK, 2>(grid, p, stream);
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
 }
 
@@ -227,15 +206,10 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begi
   // Planes per lane, measured on MI355X (config 2 / config 4, TB/s read+written): gather 1 -> 6.1 / 5.6,
   // 2 -> 5.8 / 5.9, 4 -> 5.5 / 5.7, 8 -> 3.0; scatter 1 -> 5.9 / 5.5, 2 -> 6.5 / 6.2, 4 -> 6.3 / 6.2.  One plane per
   // lane repeats the session search for every vector, which only pays off while the search is short.
-  int planes = env_int("SYMPH_MIGRATE_PLANES", (pack && n_sessions <= 64) ? 1 : 2);
-  if (planes < 1 || planes > 8 || planes == 7) planes = 2;
-  while (planes > 1 && planes > p.plane_end - p.plane_begin) --planes;
-  if (planes == 7) planes = 6;
-  const int nt = env_int("SYMPH_MIGRATE_NT", 3);  // bit 0: non-temporal loads, bit 1: non-temporal stores
+  const int planes = (pack && n_sessions <= 64) ? 1 : 2;  // (a launch always covers whole layers: two planes at least)
 
-  if (vec == 16) return pack ? launch_planes<u32x4, true>(planes, nt, p, stream) : launch_planes<u32x4, false>(planes, nt, p, stream);
-  return pack ? launch_planes<unsigned int, true>(planes, nt, p, stream)
-              : launch_planes<unsigned int, false>(planes, nt, p, stream);
+  if (vec == 16) return pack ? launch_planes<u32x4, true>(planes, p, stream) : launch_planes<u32x4, false>(planes, p, stream);
+  return pack ? launch_planes<unsigned int, true>(planes, p, stream) : launch_planes<unsigned int, false>(planes, p, stream);
 }
 
 // ------------------------------------------------------------------------------------------------------------

@@ -17,16 +17,7 @@
 // generic path (fp32, or head_dim 64): one wave per query row, lanes over keys, fp32 online softmax.
 #include "common.h"
 
-#include <stdlib.h>
-
 #include <type_traits>
-
-// Development-only: -DSYMPH_DEV_TIMERS=1 makes workgroup 0 of the MFMA kernel record per-phase shader clocks of its
-// waves into the workspace header (it overwrites the page of zeros there: timing runs only, never the product build),
-// and every workgroup a start / end record into an extra MiB at the end of the workspace.
-#ifndef SYMPH_DEV_TIMERS
-#define SYMPH_DEV_TIMERS 0
-#endif
 
 namespace symph {
 
@@ -88,30 +79,38 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const GenericParams p)
   for (int c = 0; c < D; ++c) acc[c] = 0.f;
 
   for (int32_t j = lane; j < n_keys; j += 64) {
-    const T* kp;
-    const T* vp;
+    const T* kp = nullptr;  // a block id outside the cache names a row of zeros (score 0, value 0), as in the MFMA path
+    const T* vp = nullptr;
     if (j < P) {
       const int32_t jb = j / p.block_size;
       const int32_t b = jb < p.table_stride ? p.table[(int64_t)s * p.table_stride + jb] : -1;
-      if (b < 0 || b >= p.n_blocks) continue;
-      const int64_t e = (int64_t)b * p.block_stride + ((int64_t)(j - jb * p.block_size) * p.n_kv_heads + g) * D;
-      kp = (const T*)p.k_layer + e;
-      vp = (const T*)p.v_layer + e;
+      if (b >= 0 && b < p.n_blocks) {
+        const int64_t e = (int64_t)b * p.block_stride + ((int64_t)(j - jb * p.block_size) * p.n_kv_heads + g) * D;
+        kp = (const T*)p.k_layer + e;
+        vp = (const T*)p.v_layer + e;
+      }
     } else {
       const int64_t e = ((int64_t)(cu_s + j - P) * p.n_kv_heads + g) * D;
       kp = (const T*)p.k_new + e;
       vp = (const T*)p.v_new + e;
     }
     float dot = 0.f;
+    if (kp) {
 #pragma unroll 8
-    for (int c = 0; c < D; ++c) dot = fmaf(q_s[c], to_f32(kp[c]), dot);
+      for (int c = 0; c < D; ++c) dot = fmaf(q_s[c], to_f32(kp[c]), dot);
+    }
     const float x = p.scale * dot;
     const float m_new = fmaxf(m, x);
     const float alpha = expf(m - m_new);  // m = -inf on the first key: alpha = 0
     const float w = expf(x - m_new);
     l = l * alpha + w;
+    if (vp) {
 #pragma unroll
-    for (int c = 0; c < D; ++c) acc[c] = fmaf(w, to_f32(vp[c]), acc[c] * alpha);
+      for (int c = 0; c < D; ++c) acc[c] = fmaf(w, to_f32(vp[c]), acc[c] * alpha);
+    } else {
+#pragma unroll
+      for (int c = 0; c < D; ++c) acc[c] *= alpha;
+    }
     m = m_new;
   }
 
@@ -123,7 +122,7 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const GenericParams p)
   float lt = l * f;
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) lt += __shfl_xor(lt, o);
-  const float inv = 1.0f / lt;
+  const float inv = lt > 0.f ? 1.0f / lt : 0.f;  // (every row sees at least itself, so the sum is positive)
   T* out = (T*)p.out + ((int64_t)tok * p.n_q_heads + h) * D;
 #pragma unroll
   for (int c = 0; c < D; ++c) {
@@ -146,14 +145,22 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const GenericParams p)
 // pins each kv-head to one XCD (workgroups are dealt round-robin to the 8 XCDs), so the query tiles of a session
 // that re-read the same K,V share that XCD's L2.  Chunks of a split unit write unnormalised partial results
 // (running max, running sum, accumulators) to the workspace and a merge kernel combines them.
-struct WorkItem {   // 32 bytes
-  int32_t s, t0, tile_begin, tile_end, pslot;   // pslot < 0: whole unit, write the output directly
-  int32_t cu_s, n_new, n_prefix;                // of session s, so that a workgroup starts without looking them up
+struct WorkItem {   // 64 bytes
+  int32_t s, t0, tile_begin, tile_end;
+  int32_t pslot;                  // < 0: whole unit, the workgroup writes the output rows itself
+  int32_t cu_s, n_new, n_prefix;  // of session s, so that a workgroup starts without looking them up
+  int32_t merge, pslot0, n_chunks;  // chunk of a split unit: the unit's counter, its first slot, its number of chunks
+  int32_t pad[5];
 };
-struct MergeItem {  // 16 bytes
+struct MergeItem {  // 16 bytes: a short turn that the decode kernel cut at the boundary of two shares
   int32_t s, t0, pslot0, n_chunks;
 };
-constexpr int kHdrInts = 128;    // [0..3] counts, [64..127] a 256-byte page of zeros (source of absent key rows)
+// Header of the workspace (ints): counts written by the scheduler, a counter of the decode kernel, flags, and a 256-byte
+// page of zeros (source of absent key rows).
+constexpr int kHdrInts = 128;
+constexpr int kHdrItems = 0, kHdrChunk = 1, kHdrSplitUnits = 2, kHdrPslots = 3, kHdrDecSessions = 4, kHdrDecTiles = 5,
+              kHdrDecMerges = 6, kHdrFlags = kAttnHdrFlags;
+static_assert(kHdrFlags < kAttnHdrInts && kAttnHdrInts <= 64, "the counts and flags lie in front of the zero page");
 constexpr int kZeroPageInt = 64;
 constexpr int kPartialFloats = 256 * 66;  // per workgroup: 64 accumulators + running max + running sum per thread
 
@@ -167,7 +174,7 @@ struct SchedParams {
   int32_t* dec_off;     // exclusive prefix sum of their key counts in 32-key tiles (one more entry: the total)
   int32_t* hdr;
   WorkItem* items;
-  MergeItem* merges;
+  int32_t* merge_cnt;   // [merges_bound][n_kv_heads]: chunks of a split unit that have written their partial result
 };
 
 constexpr int kBN = 64;  // keys per tile
@@ -179,70 +186,73 @@ __device__ __forceinline__ int unit_tiles(int P, int N, int t0, int bmt) {
   return (P + min(N, t0 + bmt) + kBN - 1) / kBN;
 }
 
-// Inclusive scan of one int per thread across the 256-thread block; returns the block total through `total`.
-__device__ __forceinline__ int block_inclusive_scan(int v, int* wave_sums, int& total) {
+// Inclusive scan of two ints per thread across the 256-thread block; the block totals come back through tot_a, tot_b.
+__device__ __forceinline__ void block_inclusive_scan2(int& a, int& b, int (*wave_sums)[2], int& tot_a, int& tot_b) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int incl = v;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const int up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
+    const int ua = __shfl_up(a, o), ub = __shfl_up(b, o);
+    if (lane >= o) {
+      a += ua;
+      b += ub;
+    }
   }
   __syncthreads();
-  if (lane == 63) wave_sums[w] = incl;
+  if (lane == 63) {
+    wave_sums[w][0] = a;
+    wave_sums[w][1] = b;
+  }
   __syncthreads();
-  int base = 0;
-  for (int i = 0; i < w; ++i) base += wave_sums[i];
-  total = wave_sums[0] + wave_sums[1] + wave_sums[2] + wave_sums[3];
-  return incl + base;
+  int base_a = 0, base_b = 0;
+  for (int i = 0; i < w; ++i) {
+    base_a += wave_sums[i][0];
+    base_b += wave_sums[i][1];
+  }
+  tot_a = wave_sums[0][0] + wave_sums[1][0] + wave_sums[2][0] + wave_sums[3][0];
+  tot_b = wave_sums[0][1] + wave_sums[1][1] + wave_sums[2][1] + wave_sums[3][1];
+  a += base_a;
+  b += base_b;
 }
 
-// One workgroup turns the ragged batch into the ordered work list.  All three passes run over the flat list of
-// units (session, query tile), one unit per thread per step, so a batch of one long session is as parallel as a
-// batch of many short ones.
+// One workgroup turns the ragged batch into the ordered work list.  All passes run over the flat list of units
+// (session, query tile), one unit per thread per step, so a batch of one long session is as parallel as a batch of many
+// short ones.  Which units are split, and which partial-result slots and counters their chunks get, follows from
+// prefix sums in unit order: the same for every run, and a unit for whose chunks the workspace has no room is simply
+// left whole (flag bit 0), never dropped.
 __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const SchedParams p) {
   __shared__ int unit_off[kSchedMaxSessions + 1];
-  __shared__ int wave_sums[4];
+  __shared__ int wave_sums[4][2];
   __shared__ unsigned long long total_tiles_s;
   __shared__ int hist[kSchedBuckets];
-  __shared__ int n_items_s, n_merge_s, n_pslot_s, chunk_s;
+  __shared__ int n_items_s, n_split_s, n_pslot_s, chunk_s, flags_s;
   const int tid = threadIdx.x;
   const int S = p.n_sessions;
   if (tid >= kZeroPageInt && tid < kHdrInts) p.hdr[tid] = 0;
+  for (int i = tid; i < p.merges_bound * p.n_kv_heads; i += kSchedThreads) p.merge_cnt[i] = 0;
   if (tid == 0) {
     total_tiles_s = 0ull;
     n_items_s = 0;
-    n_merge_s = 0;
+    n_split_s = 0;
     n_pslot_s = 0;
+    flags_s = 0;
   }
   if (tid < kSchedBuckets) hist[tid] = 0;
-  // unit offsets: exclusive prefix sum of ceil(N_s / bmt)
-  int carry = 0;
+  // unit offsets: exclusive prefix sum of ceil(N_s / bmt); short turns: their count and their keys in 32-key tiles
+  int U = 0, n_dec = 0, dec_total = 0;
   for (int base = 0; base < S; base += kSchedThreads) {
     const int s = base + tid;
-    const int nq = s < S ? (p.cu_new_lens[s + 1] - p.cu_new_lens[s] + p.bmt - 1) / p.bmt : 0;
-    int total;
-    const int incl = block_inclusive_scan(nq, wave_sums, total);
-    if (s < S) unit_off[s] = carry + incl - nq;
-    carry += total;
-  }
-  const int U = carry;
-  if (tid == 0) unit_off[S] = U;
-  // Short turns (1 <= N_s <= bmt_dec) are not cut into work items: the decode kernel splits the concatenation of their
-  // key ranges evenly among its workgroups, and needs their indices and the prefix sum of their lengths for that.
-  int n_dec = 0, dec_total = 0;
-  if (p.bmt_dec > 0) {
-    for (int base = 0; base < S; base += kSchedThreads) {
-      const int s = base + tid;
-      int is_dec = 0, nt = 0;
-      if (s < S) {
-        const int N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
-        is_dec = N >= 1 && N <= p.bmt_dec;
-        nt = is_dec ? (p.prefix_lens[s] + N + 31) / 32 : 0;
-      }
-      int tot_c, tot_t;
-      const int ic = block_inclusive_scan(is_dec, wave_sums, tot_c);
-      const int itl = block_inclusive_scan(nt, wave_sums, tot_t);
+    const int N = s < S ? p.cu_new_lens[s + 1] - p.cu_new_lens[s] : 0;
+    int nq = N > 0 ? (N + p.bmt - 1) / p.bmt : 0, zero = 0, tot_q, tot_z;
+    block_inclusive_scan2(nq, zero, wave_sums, tot_q, tot_z);
+    if (s < S) unit_off[s] = U + nq - (N > 0 ? (N + p.bmt - 1) / p.bmt : 0);
+    U += tot_q;
+    if (p.bmt_dec > 0) {
+      // Short turns (1 <= N_s <= bmt_dec) are not cut into work items: the decode kernel splits the concatenation of
+      // their key ranges evenly among its workgroups, and needs their indices and the prefix sum of their lengths.
+      const int is_dec = N >= 1 && N <= p.bmt_dec;
+      const int nt = is_dec ? (p.prefix_lens[s] + N + 31) / 32 : 0;
+      int ic = is_dec, itl = nt, tot_c, tot_t;
+      block_inclusive_scan2(ic, itl, wave_sums, tot_c, tot_t);
       if (is_dec) {
         p.dec_s[n_dec + ic - 1] = s;
         p.dec_off[n_dec + ic - 1] = dec_total + itl - nt;
@@ -250,22 +260,23 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
       n_dec += tot_c;
       dec_total += tot_t;
     }
-    if (tid == 0) p.dec_off[n_dec] = dec_total;
-    if (U == n_dec) {  // every unit is a short turn (each has exactly one): nothing for the work list
-      if (tid == 0) {
-        p.hdr[0] = 0;
-        p.hdr[1] = 0;
-        p.hdr[2] = 0;
-        p.hdr[3] = 0;
-        p.hdr[4] = n_dec;
-        p.hdr[5] = dec_total;
-      }
-      return;
-    }
+  }
+  if (tid == 0) {
+    unit_off[S] = U;
+    if (p.bmt_dec > 0) p.dec_off[n_dec] = dec_total;
+  }
+  if (U == n_dec) {  // every unit is a short turn (each has exactly one), or there is none: nothing for the work list
+    if (tid < 8) p.hdr[tid] = tid == kHdrDecSessions ? n_dec : (tid == kHdrDecTiles ? dec_total : 0);
+    return;
   }
   __syncthreads();
-  // unit u -> (session, first token, prefix length, new length)
-  auto unit = [&](int u, int& s, int& t0, int& P, int& N) {
+  // unit u -> tiles it has to visit (0: none, it is past the list or a short turn), with its session and lengths
+  struct Unit {
+    int s, t0, P, N, nt;
+  };
+  auto unit = [&](int u) {
+    Unit r{0, 0, 0, 0, 0};
+    if (u >= U) return r;
     int lo = 0, hi = S;  // last s with unit_off[s] <= u
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
@@ -274,19 +285,16 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
       else
         hi = mid;
     }
-    s = lo;
-    t0 = (u - unit_off[s]) * p.bmt;
-    P = p.prefix_lens[s];
-    N = p.cu_new_lens[s + 1] - p.cu_new_lens[s];
+    r.s = lo;
+    r.t0 = (u - unit_off[lo]) * p.bmt;
+    r.P = p.prefix_lens[lo];
+    r.N = p.cu_new_lens[lo + 1] - p.cu_new_lens[lo];
+    r.nt = r.N <= p.bmt_dec ? 0 : unit_tiles(r.P, r.N, r.t0, p.bmt);
+    return r;
   };
   // pass 1: total number of (unit, key tile) pairs
   unsigned long long mine = 0;
-  for (int u = tid; u < U; u += kSchedThreads) {
-    int s, t0, P, N;
-    unit(u, s, t0, P, N);
-    if (N <= p.bmt_dec) continue;
-    mine += (unsigned long long)unit_tiles(P, N, t0, p.bmt);
-  }
+  for (int u = tid; u < U; u += kSchedThreads) mine += (unsigned long long)unit(u).nt;
   if (mine) atomicAdd(&total_tiles_s, mine);
   __syncthreads();
   if (tid == 0) {
@@ -302,22 +310,55 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   }
   __syncthreads();
   const int C = chunk_s;
-  // bucket of a chunk length len in 1..C: longer chunks get smaller bucket numbers (they are dispatched first)
+  // bucket of a chunk length: longer chunks get smaller bucket numbers (they are dispatched first)
   auto bucket_of = [&](int len) {
     long long b = (long long)(C - len) * kSchedBuckets / C;
     return (int)(b < 0 ? 0 : (b >= kSchedBuckets ? kSchedBuckets - 1 : b));
   };
+  // How this thread's unit of the round starting at `base` is cut: chunks of `len` tiles, n_real of them, in slots
+  // pslot0 .. and with counter `merge` when it is split (n_real > 1).  The running totals of chunks and of split units
+  // (carry_c, carry_m) go through the rounds in unit order; a unit whose chunks would pass the end of the slots or of
+  // the counters stays whole, and so does every split candidate after it.
+  struct Cut {
+    Unit u;
+    int len, n_real, pslot0, merge;
+  };
+  auto cut_round = [&](int base, int& carry_c, int& carry_m) {
+    Cut c;
+    c.u = unit(base + tid);
+    const int nt = c.u.nt;
+    const int nc = nt > 0 ? (nt + C - 1) / C : 0;
+    c.len = nc > 0 ? (nt + nc - 1) / nc : 0;
+    c.n_real = c.len > 0 ? (nt + c.len - 1) / c.len : 0;
+    const bool want = c.n_real > 1;
+    int ic = want ? c.n_real : 0, im = want ? 1 : 0, tot_c, tot_m;
+    block_inclusive_scan2(ic, im, wave_sums, tot_c, tot_m);
+    const bool fits = carry_c + ic <= p.pslots_bound && carry_m + im <= p.merges_bound;
+    c.pslot0 = carry_c + ic - c.n_real;
+    c.merge = carry_m + im - 1;
+    if (want && !fits) {
+      c.len = nt;
+      c.n_real = 1;
+      atomicOr(&flags_s, 1);
+    }
+    if (c.n_real <= 1) {
+      c.pslot0 = -1;
+      c.merge = -1;
+    }
+    carry_c += tot_c;
+    carry_m += tot_m;
+    return c;
+  };
   // pass 2: histogram of chunk lengths
-  for (int u = tid; u < U; u += kSchedThreads) {
-    int s, t0, P, N;
-    unit(u, s, t0, P, N);
-    if (N <= p.bmt_dec) continue;
-    const int nt = unit_tiles(P, N, t0, p.bmt);
-    const int nc = (nt + C - 1) / C;
-    const int len = (nt + nc - 1) / nc;
-    const int n_full = nt / len, rem = nt - n_full * len;  // n_full chunks of len tiles and one of rem tiles
-    if (n_full) atomicAdd(&hist[bucket_of(len)], n_full);
-    if (rem) atomicAdd(&hist[bucket_of(rem)], 1);
+  {
+    int carry_c = 0, carry_m = 0;
+    for (int base = 0; base < U; base += kSchedThreads) {
+      const Cut c = cut_round(base, carry_c, carry_m);
+      if (c.n_real == 0) continue;
+      const int n_full = c.u.nt / c.len, rem = c.u.nt - n_full * c.len;  // n_full chunks of len tiles, one of rem
+      if (n_full) atomicAdd(&hist[bucket_of(c.len)], n_full);
+      if (rem) atomicAdd(&hist[bucket_of(rem)], 1);
+    }
   }
   __syncthreads();
   if (tid < kSchedBuckets) {  // wave 0: exclusive prefix sum, hist[b] becomes the first list position of bucket b
@@ -333,39 +374,38 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   }
   __syncthreads();
   // pass 3: emit items
-  for (int u = tid; u < U; u += kSchedThreads) {
-    int s, t0, P, N;
-    unit(u, s, t0, P, N);
-    if (N <= p.bmt_dec) continue;
-    const int nt = unit_tiles(P, N, t0, p.bmt);
-    const int nc = (nt + C - 1) / C;
-    const int len = (nt + nc - 1) / nc;
-    const int n_real = (nt + len - 1) / len;
-    int pslot0 = -1;
-    if (n_real > 1) {
-      pslot0 = atomicAdd(&n_pslot_s, n_real);
-      const int mi = atomicAdd(&n_merge_s, 1);
-      if (mi < p.merges_bound && pslot0 + n_real <= p.pslots_bound) {
-        p.merges[mi] = MergeItem{s, t0, pslot0, n_real};
-      } else {
-        continue;  // cannot happen while the host-side bounds hold
+  {
+    int carry_c = 0, carry_m = 0;
+    for (int base = 0; base < U; base += kSchedThreads) {
+      const Cut c = cut_round(base, carry_c, carry_m);
+      if (c.n_real == 0) continue;
+      if (c.n_real > 1) {
+        atomicMax(&n_pslot_s, c.pslot0 + c.n_real);
+        atomicMax(&n_split_s, c.merge + 1);
       }
-    }
-    for (int ch = 0; ch < n_real; ++ch) {
-      const int tb = ch * len, te = min(nt, tb + len);
-      const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
-      if (pos < p.items_bound)
-        p.items[pos] = WorkItem{s, t0, tb, te, pslot0 < 0 ? -1 : pslot0 + ch, p.cu_new_lens[s], N, P};
+      const int cu_s = p.cu_new_lens[c.u.s];
+      for (int ch = 0; ch < c.n_real; ++ch) {
+        const int tb = ch * c.len, te = min(c.u.nt, tb + c.len);
+        const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
+        if (pos < p.items_bound)
+          p.items[pos] = WorkItem{c.u.s, c.u.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, c.u.N, c.u.P,
+                                  c.merge, c.pslot0, c.n_real, {0, 0, 0, 0, 0}};
+        else
+          atomicOr(&flags_s, 2);  // more units than total_new_tokens and n_sessions allow: the lengths on the device
+                                  // disagree with the host's bounds, and this piece of work is not done
+      }
     }
   }
   __syncthreads();
   if (tid == 0) {
-    p.hdr[0] = min(n_items_s, p.items_bound);
-    p.hdr[1] = C;
-    p.hdr[2] = min(n_merge_s, p.merges_bound);
-    p.hdr[3] = n_pslot_s;
-    p.hdr[4] = n_dec;
-    p.hdr[5] = dec_total;
+    p.hdr[kHdrItems] = min(n_items_s, p.items_bound);
+    p.hdr[kHdrChunk] = C;
+    p.hdr[kHdrSplitUnits] = n_split_s;
+    p.hdr[kHdrPslots] = n_pslot_s;
+    p.hdr[kHdrDecSessions] = n_dec;
+    p.hdr[kHdrDecTiles] = dec_total;
+    p.hdr[kHdrDecMerges] = 0;
+    p.hdr[kHdrFlags] = flags_s;
   }
 }
 
@@ -385,44 +425,18 @@ struct MfmaParams {
   const int32_t* table;
   int32_t table_stride, n_sessions;
   float scale_log2e;
-  const int32_t* hdr;
+  int32_t* hdr;
   const WorkItem* items;
-  MergeItem* merges;
+  int32_t* merge_cnt;   // [split unit][kv-head]: chunks that have written their partial result
   float* partials;
   // attn_decode_kernel: the short turns' session indices and tile prefix sums (written by the scheduler), the first of
-  // its partial-result slots, and the room in the merge list
+  // its partial-result slots, its list of sessions cut at the boundary of two shares and the room in that list
   const int32_t* dec_s;
   const int32_t* dec_off;
-  int32_t dec_pslot_base, merges_bound;
-#if SYMPH_DEV_TIMERS
-  long long* dev_trace;  // per workgroup: start, end (100 MHz counter), tiles, XCC and hardware id
-#endif
+  MergeItem* dec_merges;
+  int32_t dec_pslot_base, dec_merges_bound;
 };
 
-#if SYMPH_DEV_TIMERS
-// record of workgroup b (8 x 8 bytes): 0 start, 1 end (100 MHz counter), 2 shader clocks spent << 16 | tiles,
-// 3 XCC id << 32 | hardware id, 4 / 5 start of the main loop / of the epilogue (100 MHz counter)
-__device__ __forceinline__ void dev_trace_begin(const MfmaParams& p, int rec = -1) {
-  if (rec < 0) rec = blockIdx.x;
-  if (threadIdx.x == 0) {
-    p.dev_trace[8 * rec] = wall_clock64();
-    p.dev_trace[8 * rec + 2] = clock64();
-  }
-}
-__device__ __forceinline__ void dev_trace_mark(const MfmaParams& p, int slot, int rec = -1) {
-  if (rec < 0) rec = blockIdx.x;
-  if (threadIdx.x == 0) p.dev_trace[8 * rec + slot] = wall_clock64();
-}
-__device__ __forceinline__ void dev_trace_end(const MfmaParams& p, int tiles, int rec = -1) {
-  if (rec < 0) rec = blockIdx.x;
-  if (threadIdx.x == 0) {
-    long long* t = p.dev_trace + 8 * rec;
-    t[1] = wall_clock64();
-    t[2] = ((clock64() - t[2]) << 16) | tiles;
-    t[3] = ((long long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
-  }
-}
-#endif
 
 constexpr int kD = 128;  // head_dim
 // A row sum above this (one probability of 2^40 or more, or an overflow) makes the softmax reference stale.
@@ -520,12 +534,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
+  __shared__ int merges_here;  // set for the chunk of a split unit that arrives last
   const WorkItem it = p.items[item_idx];  // the array covers the whole grid: read before the count is known
-  if (item_idx >= p.hdr[0]) return;
+  if (item_idx >= p.hdr[kHdrItems]) return;
   const int kvh = blockIdx.x - item_idx * Hkv;
-#if SYMPH_DEV_TIMERS
-  dev_trace_begin(p);
-#endif
   const int s = it.s;
   const int t0 = it.t0;
   const int cu_s = it.cu_s;
@@ -592,18 +604,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   };
   // Issue the loads of one tile of K or of V into an LDS buffer.  Rows that do not exist (past the session's keys, or
   // named by a block id outside the cache) are read from the page of zeros, so they are finite and add nothing.
-#if SYMPH_DEV_TIMERS
-  long long dev_dma = 0;  // clocks inside the fast path's four loads
-#endif
   auto issue_tile = [&](const char* pool_bytes, const __bf16* new_rows, char* lds_buf, int tile) {
     // one comparison of the largest id (as unsigned: a negative id is huge)
     const unsigned id_max = max(max((unsigned)ids[0], (unsigned)ids[1]), max((unsigned)ids[2], (unsigned)ids[3]));
     const bool fast = tile < fast_end && id_max < (unsigned)p.n_blocks;
     if (__builtin_expect(fast, 1)) {
-#if SYMPH_DEV_TIMERS
-      asm volatile("" ::: "memory");
-      const long long dma0 = clock64();
-#endif
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         uint64_t off = (uint64_t)(unsigned)ids[i] * p.block_bytes;
@@ -617,9 +622,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         SYMPH_GLDS16(base + lane_off, lds_buf + (4 * i + wave) * kGroupBytes);
       }
       asm volatile("; end of the scalar-base loads");  // keeps the last one from being merged with the other path's
-#if SYMPH_DEV_TIMERS
-      dev_dma += clock64() - dma0;
-#endif
     } else {
       // rare path: its per-lane address pieces are derived here, from a lane id the optimiser cannot see through, so
       // that they do not occupy registers throughout the main loop
@@ -776,10 +778,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   // A wave issues in order, so the instruction stream itself has to alternate between the two kinds; the
   // sched_group_barrier sequences ask the scheduler for that interleaving and for LDS reads that run several matrix
   // instructions ahead of their use (a read issued right before its MFMA exposes the full LDS latency every time).
-#if SYMPH_DEV_TIMERS
-  long long dev_ph[4] = {0, 0, 0, 0};
-  const long long dev_c0 = clock64();
-#endif
   f32x16 s_even[2], s_odd[2];  // scores of the even and of the odd tiles (counted from tile_begin)
   int ids_v[4];  // ids of the tile whose V rows are loaded next
   {
@@ -806,6 +804,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   mask(s_even, tile_begin);
   raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile
   softmax_exp_half(s_even[0], mb_cur, pb[0]);
+  // Every wave has read all of K0 for the first product before any wave overwrites it: the first iteration loads
+  // K(tile_begin + 2) into K0.  (Later iterations are ordered by the barrier at their end.)
+  __syncthreads();
 
   auto iteration = [&](const int j, auto par_c) {
     constexpr int PAR = decltype(par_c)::value;
@@ -815,9 +816,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     char* const v_other = PAR ? V0 : V1;  // held V(j-1), free now: receives V(j+1)
     f32x16 (&s_cur)[2] = PAR ? s_odd : s_even;   // S(j)
     f32x16 (&s_nxt)[2] = PAR ? s_even : s_odd;   // receives S(j+1)
-#if SYMPH_DEV_TIMERS
-    const long long ph0 = clock64();
-#endif
     if (j + 1 < tile_end) {
       int keep[4];
 #pragma unroll
@@ -827,9 +825,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       for (int i = 0; i < 4; ++i) ids[i] = keep[i];
     }
     if (j + 2 < tile_end) issue_tile(k_bytes, p.k_new, k_same, j + 2);
-#if SYMPH_DEV_TIMERS
-    const long long ph1 = clock64();
-#endif
     // ---- block A
     qk(k_other, s_nxt);                          // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
     softmax_exp_half(s_cur[1], mb_cur, pb[1]);   // second half of P(j)
@@ -849,10 +844,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[kb][u]));
     asm volatile("" : "+v"(ps));
-#if SYMPH_DEV_TIMERS
-    asm volatile("s_nop 0" ::: "memory");
-    const long long ph2 = clock64();
-#endif
     // The reference is stale when some score exceeds it by more than 40 in log2 units (then the row sum is huge,
     // infinite or NaN), or when a row that had seen no key now has one.  Rare: redo this tile's probabilities from
     // its scores, which are still in registers, against a refreshed reference.
@@ -893,17 +884,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     pb[0][0] = pb_first[0];   // (garbage, and never used, when there was no tile j+1)
     pb[0][1] = pb_first[1];
     asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]));   // computed here, not after the barrier
-#if SYMPH_DEV_TIMERS
-    asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
-    const long long ph3 = clock64();
-#endif
 #pragma unroll
     for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];      // the next V tile is j+2
     wait_loads_and_sync();
-#if SYMPH_DEV_TIMERS
-    const long long ph4 = clock64();
-    dev_ph[0] += ph1 - ph0; dev_ph[1] += ph2 - ph1; dev_ph[2] += ph3 - ph2; dev_ph[3] += ph4 - ph3;
-#endif
   };
   // Before each iteration the ids fetched an iteration ago become scalar and the fetch of the next ones starts (it
   // completes under the wait at the end of the iteration).
@@ -912,22 +895,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     fetch_ids(j + 3);   // index clamped to the table: harmless past the last tile
     iteration(j, par_c);
   };
-#if SYMPH_DEV_TIMERS
-  dev_trace_mark(p, 4);
-#endif
   for (int j = tile_begin; j < tile_end; j += 2) {
     step(j, std::integral_constant<int, 0>{});
     if (j + 1 < tile_end) step(j + 1, std::integral_constant<int, 1>{});
   }
 
-#if SYMPH_DEV_TIMERS
-  dev_trace_mark(p, 5);
-  if (blockIdx.x == 0 && (tid & 63) == 0) {  // per-phase shader clocks of each wave of workgroup 0
-    long long* t = reinterpret_cast<long long*>(const_cast<int32_t*>(p.hdr) + 16) + 8 * (tid >> 6);
-    t[0] = dev_ph[0]; t[1] = dev_ph[1]; t[2] = dev_ph[2]; t[3] = dev_ph[3]; t[4] = clock64() - dev_c0; t[5] = tile_end - tile_begin;
-    t[6] = dev_dma;
-  }
-#endif
   if (it.pslot < 0) {
     const float l_tot = sum_across_halves(l_run);
     if (q_valid)
@@ -941,10 +913,40 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       for (int e = 0; e < 16; ++e) part[(dt * 16 + e) * 256] = o_acc[dt][e];
     part[64 * 256] = m_run;
     part[65 * 256] = l_run;
+    // The chunk that arrives last combines all of them (no further kernel): every thread makes its stores visible
+    // to the device, then one thread counts this chunk in.
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) merges_here = atomicAdd(p.merge_cnt + (int64_t)it.merge * Hkv + kvh, 1) == it.n_chunks - 1;
+    __syncthreads();
+    if (!merges_here) return;
+    __threadfence();
+    // out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being chunk c's softmax reference in log2
+    // units (-inf: the chunk saw no key of the row).  All chunks are read back in chunk order, this one's too, so the
+    // result does not depend on which chunk came last.  Same thread -> (row, d) mapping as the dump above.
+    const float* first = p.partials + ((int64_t)it.pslot0 * Hkv + kvh) * kPartialFloats + tid;
+    const int64_t chunk_stride = (int64_t)Hkv * kPartialFloats;
+    float M = -INFINITY;
+    for (int ch = 0; ch < it.n_chunks; ++ch) M = fmaxf(M, first[ch * chunk_stride + 64 * 256]);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o_acc[dt][e] = 0.f;
+    float L = 0.f;
+    for (int ch = 0; ch < it.n_chunks; ++ch) {
+      const float* src = first + ch * chunk_stride;
+      const float mc = src[64 * 256];
+      const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);
+      L += w * src[65 * 256];
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[dt][e] = fmaf(w, src[(dt * 16 + e) * 256], o_acc[dt][e]);
+    }
+    const float l_tot = sum_across_halves(L);
+    if (q_valid)
+      store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + head) * kD, o_acc, 1.0f / l_tot, g2);
   }
-#if SYMPH_DEV_TIMERS
-  dev_trace_end(p, 2 * (tile_end - tile_begin));
-#endif
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -977,15 +979,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
   const int Hkv = p.n_kv_heads;
   const int wg = blockIdx.x / Hkv;
   const int kvh = blockIdx.x - wg * Hkv;
-  const int n_dec = p.hdr[4];
-  const int total = p.hdr[5];
+  const int n_dec = p.hdr[kHdrDecSessions];
+  const int total = p.hdr[kHdrDecTiles];
   const int per_wg = (total + (int)(gridDim.x / Hkv) - 1) / (int)(gridDim.x / Hkv);
   const int range_begin = wg * per_wg;
   const int range_end = min(total, range_begin + per_wg);
   if (range_begin >= range_end) return;
-#if SYMPH_DEV_TIMERS
-  dev_trace_begin(p, 8192 + blockIdx.x);  // the decode kernel's records follow the main kernel's
-#endif
   const int lb = LB ? LB : p.log_bs;
   const int bs_mask = (1 << lb) - 1;
   const int tid = threadIdx.x;
@@ -1213,21 +1212,11 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
       issue_half(0, u, ids);
       issue_half(1, u, ids);
     }
-#if SYMPH_DEV_TIMERS
-    long long dev_t[3] = {0, 0, 0};
-    int dev_n = 0;
-#endif
     for (; u < u_end; u += 4) {
       const bool more = u + 4 < u_end;
       const Ids ids_next = fetch_ids(u + 4);
-#if SYMPH_DEV_TIMERS
-      const long long c0 = clock64();
-#endif
       __builtin_amdgcn_s_waitcnt(0x0F70 | 8);  // vmcnt(8): K(u) has landed, V(u) may be on its way
       asm volatile("" ::: "memory");
-#if SYMPH_DEV_TIMERS
-      const long long c1 = clock64();
-#endif
       scores_of_tile(u, first);
       first = false;
       asm volatile("" ::: "memory");
@@ -1240,18 +1229,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
       values_of_tile();
       asm volatile("" ::: "memory");
       if (more) issue_half(1, u + 4, ids_next);
-#if SYMPH_DEV_TIMERS
-      asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
-      const long long c3 = clock64();
-      dev_t[1] += c1 - c0; dev_t[2] += c3 - c1; ++dev_n;
-#endif
     }
-#if SYMPH_DEV_TIMERS
-    if (blockIdx.x == 8 * 5 && lane == 0) {  // one workgroup: per-wave clocks spent waiting for K, and on the rest
-      long long* t = p.dev_trace + (1 << 17) - 64 + 8 * wave;
-      t[0] = dev_t[0]; t[1] = dev_t[1]; t[2] = dev_t[2]; t[3] = dev_n;
-    }
-#endif
   }
 
   // ---- combine the four waves: wave w ends up with the d-slice 32w .. 32w+31 of the 32 rows
@@ -1304,8 +1282,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
     const int pslot = p.dec_pslot_base + 2 * wg + (at_range_start ? 0 : 1);
     if (u_begin == 0 && kvh == 0 && tid == 0) {
       const int last_wg = (unit_end - 1) / per_wg;
-      const int mi = atomicAdd(const_cast<int32_t*>(p.hdr) + 2, 1);
-      if (mi < p.merges_bound) p.merges[mi] = MergeItem{s, 0, pslot, -(last_wg - wg + 1)};
+      const int mi = atomicAdd(p.hdr + kHdrDecMerges, 1);  // at most one per workgroup: the list has room for all
+      if (mi < p.dec_merges_bound) p.dec_merges[mi] = MergeItem{s, 0, pslot, last_wg - wg + 1};
     }
     // the merge kernel's layout: thread (row >> 5) * 64 + g2 * 32 + (row & 31) with row = head * BMT + token
     const int row = hh * BMT + tt;
@@ -1319,24 +1297,23 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
   }
   __syncthreads();  // the exchange area becomes tile buffers again
   }
-#if SYMPH_DEV_TIMERS
-  dev_trace_end(p, range_end - range_begin, 8192 + blockIdx.x);
-#endif
 }
 
-// Combine the chunks of a split unit: out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being the
-// chunk's softmax reference in log2 units (-inf: the chunk saw no key of the row).
-// One workgroup per (unit, kv-head, 32-wide slice of d), same thread -> (row, d) mapping as the main kernel.
+// Combine the pieces of a short turn that the decode kernel cut at the boundaries of its workgroups' shares:
+// out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being the piece's softmax reference in log2
+// units (-inf: the piece saw no key of the row).  The first piece is in pslot0, piece c >= 1 in the even slot of the
+// c-th workgroup after the one that wrote pslot0.
+// One workgroup per (session, kv-head, 32-wide slice of d), same thread -> (row, d) mapping as attn_mfma_kernel.
 template <int G>
-__global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
+__global__ __launch_bounds__(256) void attn_decode_merge_kernel(const MfmaParams p) {
   constexpr int BMT = 128 / G;
   const int Hkv = p.n_kv_heads;
   const int dt = blockIdx.x & 3;
   const int rest = blockIdx.x >> 2;
   const int mi = rest / Hkv;
-  if (mi >= p.hdr[2]) return;
+  if (mi >= min(p.hdr[kHdrDecMerges], p.dec_merges_bound)) return;
   const int kvh = rest - mi * Hkv;
-  const MergeItem m = p.merges[mi];
+  const MergeItem m = p.dec_merges[mi];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int n = lane & 31, g2 = lane >> 5;
@@ -1345,24 +1322,21 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
   const int tok = m.t0 + (r - hh * BMT);
   const int cu_s = p.cu_new_lens[m.s];
   const int N = p.cu_new_lens[m.s + 1] - cu_s;
-  // chunk ch of a unit: slot pslot0 + ch; of a short turn cut by the decode kernel (negative count): its first piece
-  // in pslot0, piece ch >= 1 in the even slot of the ch-th workgroup after the one that wrote pslot0
-  const int n_chunks = m.n_chunks < 0 ? -m.n_chunks : m.n_chunks;
   const int first_wg = (m.pslot0 - p.dec_pslot_base) >> 1;
   auto chunk = [&](int ch) {
-    const int slot = (m.n_chunks > 0 || ch == 0) ? m.pslot0 + ch : p.dec_pslot_base + 2 * (first_wg + ch);
+    const int slot = ch == 0 ? m.pslot0 : p.dec_pslot_base + 2 * (first_wg + ch);
     return p.partials + ((int64_t)slot * Hkv + kvh) * kPartialFloats + tid;
   };
   // Rows past the session's new tokens hold nothing (a one-token turn fills 4 of a slot's 128 rows): their lanes, in
   // pairs l and l ^ 32 (the two halves of one row), read no partial results.  No barrier follows.
   if (tok >= N) return;
   float M = -INFINITY;
-  for (int ch = 0; ch < n_chunks; ++ch) M = fmaxf(M, chunk(ch)[64 * 256]);
+  for (int ch = 0; ch < m.n_chunks; ++ch) M = fmaxf(M, chunk(ch)[64 * 256]);
   float acc[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   float L = 0.f;
-  for (int ch = 0; ch < n_chunks; ++ch) {
+  for (int ch = 0; ch < m.n_chunks; ++ch) {
     const float* part = chunk(ch);
     const float mc = part[64 * 256];
     const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);  // references are in log2 units
@@ -1371,68 +1345,102 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MfmaParams p) {
     for (int e = 0; e < 16; ++e) acc[e] = fmaf(w, part[(dt * 16 + e) * 256], acc[e]);
   }
   const float l_tot = sum_across_halves(L);
-  if (tok < N) {
-    const float inv = 1.0f / l_tot;
-    __bf16* op = p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + (kvh * G + hh)) * kD;
+  const float inv = 1.0f / l_tot;
+  __bf16* op = p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + (kvh * G + hh)) * kD;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      bf16x4 v;
+  for (int i = 0; i < 4; ++i) {
+    bf16x4 v;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = (__bf16)(acc[4 * i + j] * inv);
-      *reinterpret_cast<bf16x4*>(op + 32 * dt + 4 * g2 + 8 * i) = v;
-    }
+    for (int j = 0; j < 4; ++j) v[j] = (__bf16)(acc[4 * i + j] * inv);
+    *reinterpret_cast<bf16x4*>(op + 32 * dt + 4 * g2 + 8 * i) = v;
   }
 }
 
 // ------------------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------------------
-static int env_int(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
+// Tuning values with the defaults filled in (a field of symph_attn_tuning that is 0 keeps its default).
+struct AttnTuning {
+  int32_t slots, c_min, coarse, decode, decode_wgs;
+};
+static AttnTuning resolve_tuning(const symph_attn_tuning* t) {
+  AttnTuning r{512, 8, 1, 1, 512};  // 512 slots: 256 compute units x 2 resident workgroups
+  if (t) {
+    if (t->slots > 0) r.slots = t->slots;
+    if (t->c_min > 0) r.c_min = t->c_min;
+    if (t->coarse != 0) r.coarse = t->coarse > 0;
+    if (t->decode != 0) r.decode = t->decode > 0;
+    if (t->decode_wgs > 0) r.decode_wgs = t->decode_wgs;
+  }
+  return r;
 }
 
 struct MfmaPlan {
-  int32_t bmt, target, target_slots, c_min, units_bound, items_bound, merges_bound, pslots_bound;
-  int32_t dec_wgs, dec_pslot_base;  // decode kernel: workgroups per kv-head, first of their 2 * dec_wgs slots
-  int64_t off_items, off_dec_s, off_dec_off, off_merges, off_partials, total_bytes;
+  int32_t bmt, target, target_slots, c_min, coarse, units_bound, items_bound, merges_bound, pslots_bound;
+  // decode kernel: whether this call runs it, workgroups per kv-head, first of their 2 * dec_wgs slots, room in its
+  // list of sessions cut between shares
+  int32_t dec_mode, dec_wgs, dec_pslot_base, dec_merges_bound;
+  int64_t off_items, off_dec_s, off_dec_off, off_dec_merges, off_merge_cnt, off_partials, total_bytes;
 };
 
 static inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
-// Sizes that depend only on host-visible bounds, so that the workspace query and the launch agree.
-static MfmaPlan make_plan(int32_t n_sessions, int32_t n_q_heads, int32_t n_kv_heads, int32_t total_new_tokens) {
-  MfmaPlan pl;
-  const int G = n_q_heads / n_kv_heads;
-  pl.bmt = 128 / G;
-  pl.target_slots = env_int("SYMPH_ATTN_SLOTS", 512);  // workgroups resident at once: 256 CUs x 2
-  if (pl.target_slots < n_kv_heads) pl.target_slots = n_kv_heads;
-  pl.target = 2 * pl.target_slots;                     // most pieces the batch is ever cut into (two per slot)
-  pl.c_min = env_int("SYMPH_ATTN_CMIN", 8);
-  if (pl.c_min < 1) pl.c_min = 1;
-  pl.units_bound = total_new_tokens / pl.bmt + n_sessions;
-  const int32_t per_head = pl.target / n_kv_heads + 1;
-  pl.items_bound = pl.units_bound + per_head;
-  pl.merges_bound = per_head;
-  pl.pslots_bound = 2 * per_head;
-  // decode kernel (batches of short turns only): one equal share of the keys per workgroup, two partial-result slots
-  // and at most one entry of the merge list per workgroup
-  pl.dec_wgs = env_int("SYMPH_ATTN_DECODE_WGS", 512) / n_kv_heads;
-  if (pl.dec_wgs < 1) pl.dec_wgs = 1;
+static void lay_out(MfmaPlan& pl, int32_t n_sessions, int32_t n_kv_heads) {
+  pl.items_bound = pl.units_bound + pl.pslots_bound;  // every unit once, plus one more item per chunk of a split unit
+  pl.merges_bound = pl.pslots_bound / 2;              // a split unit has at least two chunks
   pl.dec_pslot_base = pl.pslots_bound;
-  pl.pslots_bound += 2 * pl.dec_wgs;
-  pl.merges_bound += pl.dec_wgs;
+  pl.dec_merges_bound = pl.dec_wgs;                   // at most one session starts inside a share and leaves it
   const int32_t ns = n_sessions < kSchedMaxSessions ? n_sessions : kSchedMaxSessions;  // per scheduler slice
   pl.off_items = align256(kHdrInts * 4);
   pl.off_dec_s = align256(pl.off_items + (int64_t)pl.items_bound * sizeof(WorkItem));
   pl.off_dec_off = align256(pl.off_dec_s + (int64_t)ns * 4);
-  pl.off_merges = align256(pl.off_dec_off + (int64_t)(ns + 1) * 4);
-  pl.off_partials = align256(pl.off_merges + (int64_t)pl.merges_bound * sizeof(MergeItem));
-  pl.total_bytes = pl.off_partials + (int64_t)pl.pslots_bound * n_kv_heads * kPartialFloats * 4;
-#if SYMPH_DEV_TIMERS
-  pl.total_bytes = align256(pl.total_bytes) + (1 << 20);
-#endif
-  return pl;
+  pl.off_dec_merges = align256(pl.off_dec_off + (int64_t)(ns + 1) * 4);
+  pl.off_merge_cnt = align256(pl.off_dec_merges + (int64_t)pl.dec_merges_bound * sizeof(MergeItem));
+  pl.off_partials = align256(pl.off_merge_cnt + (int64_t)pl.merges_bound * n_kv_heads * 4);
+  pl.total_bytes = pl.off_partials + (int64_t)(pl.pslots_bound + 2 * pl.dec_wgs) * n_kv_heads * kPartialFloats * 4;
+}
+
+// Sizes that depend only on host-visible bounds and the tuning values, so that the workspace query and the launch
+// agree.  budget_bytes > 0: the plan has to fit that many bytes; the decode kernel then gets fewer workgroups and the
+// work list is cut into fewer pieces (fewer partial-result slots).  Returns false if not even the uncut list fits.
+static bool make_plan(MfmaPlan& pl, int32_t n_sessions, int32_t n_q_heads, int32_t n_kv_heads,
+                      int32_t total_new_tokens, int32_t max_new_len, const AttnTuning& tu, int64_t budget_bytes) {
+  const int G = n_q_heads / n_kv_heads;
+  pl.bmt = 128 / G;
+  pl.target_slots = tu.slots < n_kv_heads ? n_kv_heads : tu.slots;  // workgroups resident at once
+  pl.target = 2 * pl.target_slots;                                  // most pieces the batch is ever cut into
+  pl.c_min = tu.c_min;
+  pl.coarse = tu.coarse;
+  pl.units_bound = total_new_tokens / pl.bmt + n_sessions;
+  // A batch in which no session has more new rows than one wave holds (decode steps) takes the decode kernel: one
+  // equal share of the keys per workgroup, two partial-result slots per workgroup.  Mixed batches do not: their short
+  // turns are memory-bound pieces that share the CUs with the compute-bound ones inside the main kernel, which
+  // measured faster than two kernels one after the other.
+  pl.dec_mode = tu.decode && max_new_len >= 1 && max_new_len * G <= 32;
+  pl.dec_wgs = pl.dec_mode ? (tu.decode_wgs / n_kv_heads < 1 ? 1 : tu.decode_wgs / n_kv_heads) : 0;
+  // Chunks of split units: a unit is split when it has more than C tiles, C >= total tiles * kv-heads / target, so
+  // there are at most target / kv-heads split units and their chunks number at most twice that.
+  pl.pslots_bound = 2 * (pl.target / n_kv_heads + 1);
+  lay_out(pl, n_sessions, n_kv_heads);
+  if (budget_bytes <= 0 || pl.total_bytes <= budget_bytes) return true;
+  const int64_t slot_bytes = (int64_t)n_kv_heads * kPartialFloats * 4;
+  while (pl.dec_wgs > 1 && pl.total_bytes > budget_bytes) {
+    pl.dec_wgs /= 2;
+    lay_out(pl, n_sessions, n_kv_heads);
+  }
+  if (pl.total_bytes > budget_bytes) {
+    pl.pslots_bound = 0;
+    lay_out(pl, n_sessions, n_kv_heads);
+    const int64_t per_slot = slot_bytes + (int64_t)sizeof(WorkItem) + 4 * n_kv_heads;
+    const int64_t room = budget_bytes - pl.total_bytes - 4 * 256;  // (the arrays are aligned to 256 bytes)
+    if (room < 0) return false;
+    pl.pslots_bound = (int32_t)(room / per_slot < 0x7FFFFFFF ? room / per_slot : 0x7FFFFFFF) & ~1;
+    const int64_t pieces = (int64_t)(pl.pslots_bound / 2) * n_kv_heads;  // (the bound above, solved for the target)
+    if (pieces < pl.target) pl.target = pieces < n_kv_heads ? n_kv_heads : (int32_t)pieces;
+    if (pl.target_slots > pl.target) pl.target_slots = pl.target;
+    lay_out(pl, n_sessions, n_kv_heads);
+  }
+  return pl.total_bytes <= budget_bytes;
 }
 
 static bool mfma_path_ok(int32_t dtype, int32_t head_dim, int32_t n_q_heads, int32_t n_kv_heads, int32_t block_size) {
@@ -1443,10 +1451,13 @@ static bool mfma_path_ok(int32_t dtype, int32_t head_dim, int32_t n_q_heads, int
 }
 
 int64_t prefill_attn_workspace_bytes(const symph_kv_cache* c, int32_t n_sessions, int32_t n_q_heads,
-                                     int32_t total_new_tokens, int32_t, int32_t) {
+                                     int32_t total_new_tokens, int32_t max_new_len, int32_t,
+                                     const symph_attn_tuning* tuning) {
   if (n_q_heads % c->n_kv_heads != 0) return -1;
   if (!mfma_path_ok(c->dtype, c->head_dim, n_q_heads, c->n_kv_heads, c->block_size)) return 0;
-  return make_plan(n_sessions, n_q_heads, c->n_kv_heads, total_new_tokens).total_bytes;
+  MfmaPlan pl;
+  make_plan(pl, n_sessions, n_q_heads, c->n_kv_heads, total_new_tokens, max_new_len, resolve_tuning(tuning), 0);
+  return pl.total_bytes;
 }
 
 template <typename T, int D>
@@ -1478,10 +1489,15 @@ static int32_t launch_generic(const AttnArgs& a, hipStream_t stream) {
 
 template <int G>
 static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
-  const MfmaPlan pl = make_plan(a.n_sessions, a.n_q_heads, a.n_kv_heads, a.total_new_tokens);
-  if (!a.workspace || a.workspace_bytes < pl.total_bytes) return SYMPH_EWORKSPACE;
-  if (((uintptr_t)a.workspace & 255) != 0) return SYMPH_EUNSUPPORTED;
+  MfmaPlan pl;
+  const AttnTuning tu = resolve_tuning(a.tuning);
   char* ws = (char*)a.workspace;
+  // fit_workspace: the caller's buffer has a fixed size and the plan is made to fit it (a coarser cut of the work list)
+  if (!make_plan(pl, a.n_sessions, a.n_q_heads, a.n_kv_heads, a.total_new_tokens, a.max_new_len, tu,
+                 a.fit_workspace ? a.workspace_bytes : 0) ||
+      !ws || a.workspace_bytes < pl.total_bytes)
+    return SYMPH_EWORKSPACE;
+  if (((uintptr_t)ws & 255) != 0) return SYMPH_EUNSUPPORTED;
 
   SchedParams sp;
   sp.cu_new_lens = a.cu_new_lens;
@@ -1491,21 +1507,17 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   sp.n_kv_heads = a.n_kv_heads;
   sp.target = pl.target;
   sp.target_slots = pl.target_slots;
-  sp.coarse_ok = env_int("SYMPH_ATTN_COARSE", 1);
+  sp.coarse_ok = pl.coarse;
   sp.c_min = pl.c_min;
   sp.items_bound = pl.items_bound;
-  sp.merges_bound = pl.merges_bound - pl.dec_wgs;  // the work items' share; the rest is the decode kernel's
-  sp.pslots_bound = pl.dec_pslot_base;
+  sp.merges_bound = pl.merges_bound;
+  sp.pslots_bound = pl.pslots_bound;
   sp.hdr = (int32_t*)ws;
-  // A batch in which no session has more new rows than one wave holds (decode steps) takes the decode kernel.  Mixed
-  // batches do not: their short turns are memory-bound pieces that share the CUs with the compute-bound ones inside
-  // the main kernel, which measured faster than two kernels one after the other.
-  const bool dec_mode = env_int("SYMPH_ATTN_DECODE", 1) != 0 && a.max_new_len >= 1 && a.max_new_len * G <= 32;
-  sp.bmt_dec = dec_mode ? 32 / G : 0;
+  sp.bmt_dec = pl.dec_mode ? 32 / G : 0;
   sp.dec_s = (int32_t*)(ws + pl.off_dec_s);
   sp.dec_off = (int32_t*)(ws + pl.off_dec_off);
   sp.items = (WorkItem*)(ws + pl.off_items);
-  sp.merges = (MergeItem*)(ws + pl.off_merges);
+  sp.merge_cnt = (int32_t*)(ws + pl.off_merge_cnt);
 
   MfmaParams p;
   p.k_layer = (const __bf16*)a.k_layer;
@@ -1529,23 +1541,18 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.hdr = sp.hdr;
   p.items = sp.items;
+  p.merge_cnt = sp.merge_cnt;
   p.dec_s = sp.dec_s;
   p.dec_off = sp.dec_off;
+  p.dec_merges = (MergeItem*)(ws + pl.off_dec_merges);
   p.dec_pslot_base = pl.dec_pslot_base;
-  p.merges_bound = pl.merges_bound;
-  p.merges = sp.merges;
+  p.dec_merges_bound = pl.dec_merges_bound;
   p.partials = (float*)(ws + pl.off_partials);
-#if SYMPH_DEV_TIMERS
-  p.dev_trace = (long long*)(ws + pl.total_bytes - (1 << 20));
-#endif
 
   const int64_t g_main = (int64_t)pl.items_bound * a.n_kv_heads;
-  const int64_t g_merge = (int64_t)pl.merges_bound * a.n_kv_heads * 4;
-  const int64_t g_dec = dec_mode ? (int64_t)pl.dec_wgs * a.n_kv_heads : 0;
-  if (g_main > 0x7FFFFFFFLL || g_dec > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
-#if SYMPH_DEV_TIMERS
-  if (g_main > 8192 || (8192 + g_dec) * 64 > (1 << 20) - 512) return SYMPH_EUNSUPPORTED;
-#endif
+  const int64_t g_dec = (int64_t)pl.dec_wgs * a.n_kv_heads;
+  const int64_t g_merge = (int64_t)pl.dec_merges_bound * a.n_kv_heads * 4;
+  if (g_main > 0x7FFFFFFFLL || g_merge > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
   // The scheduler keeps one table entry per session in LDS: larger batches run as consecutive slices of sessions
   // (same stream, same workspace; the bounds of the whole batch cover every slice).
   for (int32_t s0 = 0; s0 < a.n_sessions; s0 += kSchedMaxSessions) {
@@ -1558,19 +1565,19 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
     p.table = a.table ? a.table + (int64_t)s0 * a.table_stride : nullptr;
     p.n_sessions = ns;
     hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
-    // (Launched for decode-only batches too, where its work list is empty if max_new_len was a true bound: a session
-    // longer than the caller stated is then still computed, by this kernel, instead of being dropped.)
+    // The work-item kernel runs for decode steps too.  Its list is then empty if max_new_len was a true bound; a
+    // session with more new tokens than the caller stated is not a short turn for the scheduler and is computed here.
     if (a.block_size == 16)
       hipLaunchKernelGGL((attn_mfma_kernel<G, 4>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
     else
       hipLaunchKernelGGL((attn_mfma_kernel<G, 0>), dim3((unsigned)g_main), dim3(256), 0, stream, p);
-    if (g_dec > 0) {
+    if (pl.dec_mode) {
       if (a.block_size == 16)
         hipLaunchKernelGGL((attn_decode_kernel<G, 4>), dim3((unsigned)g_dec), dim3(256), 0, stream, p);
       else
         hipLaunchKernelGGL((attn_decode_kernel<G, 0>), dim3((unsigned)g_dec), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL((attn_decode_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
     }
-    hipLaunchKernelGGL((attn_merge_kernel<G>), dim3((unsigned)g_merge), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
 }

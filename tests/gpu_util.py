@@ -51,19 +51,24 @@ def gpu_unpack(cache: S.KVCache, ds: DeviceSessions, buf: torch.Tensor, dst: boo
                 buf, stream=stream)
 
 
-def gpu_attention(cfg: W.WorkloadConfig, sess: W.SessionBatch, inputs, layer: int = 0, scale=None) -> np.ndarray:
-    """Run symph_prefix_prefill_attn on host inputs (one-layer pools) and return the output as numpy."""
+def gpu_attention(cfg: W.WorkloadConfig, sess: W.SessionBatch, inputs, layer: int = 0, scale=None, tuning=None,
+                  max_new_len=None, expect_flags: int = 0) -> np.ndarray:
+    """Run symph_prefix_prefill_attn on host inputs (one-layer pools) and return the output as numpy.  ``tuning``: an
+    S.AttnTuning for the _tuned entry points; ``max_new_len``: the bound handed to the library when it is not the true
+    one.  The scheduler's flags are read back after every call and must be ``expect_flags``."""
     k_pool, v_pool, q, k_new, v_new = inputs
     ds = DeviceSessions(sess)
     cache = S.KVCache(to_dev(k_pool)[None], to_dev(v_pool)[None])
     qd, knd, vnd = to_dev(q), to_dev(k_new), to_dev(v_new)
     out = torch.full_like(qd, float("nan"))
+    mnl = sess.max_new_len if max_new_len is None else max_new_len
     ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
-                                                     sess.max_new_len, sess.max_prefix_len)
+                                                     mnl, sess.max_prefix_len, tuning=tuning)
     ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=DEV) if ws_bytes else None
     S.prefix_prefill_attn(cache, layer, qd, knd, vnd, out, ds.cu_new_lens, ds.prefix_lens, ds.table,
-                          sess.max_new_len, sess.max_prefix_len, cfg.scale if scale is None else scale, workspace=ws)
+                          mnl, sess.max_prefix_len, cfg.scale if scale is None else scale, workspace=ws, tuning=tuning)
     torch.cuda.synchronize()
+    assert S.debug_attn_flags(ws) == expect_flags, "the device-side scheduler reported a problem"
     return to_host(out)
 
 

@@ -7,18 +7,19 @@ thousands of Gaussian keys gives outputs of magnitude ~1e-2, every case is ALSO 
 import numpy as np
 import pytest
 
+import paper_2412_16434_amd as S
 import workloads as W
 from gpu_util import TOL, attn_errors, gpu_attention, widen
 
 pytestmark = pytest.mark.gpu
 
 
-def check(oracle_mod, cfg, sess, inputs, token_subset=None, scale=None, label=""):
+def check(oracle_mod, cfg, sess, inputs, token_subset=None, scale=None, label="", **gpu_kw):
     k_pool, v_pool, q, k_new, v_new = inputs
     sc = cfg.scale if scale is None else scale
     ref = oracle_mod.prefix_prefill_attn(k_pool, v_pool, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
                                          sess.block_table, sc, token_subset=token_subset)
-    got = gpu_attention(cfg, sess, inputs, scale=sc)
+    got = gpu_attention(cfg, sess, inputs, scale=sc, **gpu_kw)
     assert got.shape == ref.shape
     assert np.all(np.isfinite(widen(got))), "non-finite values in the GPU output"
     max_abs, rel = attn_errors(got, ref)
@@ -98,29 +99,54 @@ def test_attention_edge_cases(oracle_mod, kw):
     (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 0, 3), block_size=32, n_blocks=256, n_sessions=10), 32),
     (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 3), block_size=64, n_blocks=128, n_sessions=10), 512),
 ])
-def test_decode_batches(oracle_mod, monkeypatch, kw, n_wgs):
-    monkeypatch.setenv("SYMPH_ATTN_DECODE_WGS", str(n_wgs))
+def test_decode_batches(oracle_mod, kw, n_wgs):
     cfg = _cfg(**kw)
     sess = W.make_sessions(cfg, 37)
-    check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 37), label=f"decode batch, {n_wgs} shares")
+    check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 37), label=f"decode batch, {n_wgs} shares",
+          tuning=S.AttnTuning(decode_wgs=n_wgs))
 
 
-def test_decode_batch_agrees_with_the_work_item_path(oracle_mod, monkeypatch):
+def test_decode_batch_agrees_with_the_work_item_path(oracle_mod):
     """The same decode-shaped batch through the decode kernel and (switched off) through the main kernel."""
     cfg = _cfg(prefix_dist=("uniform", 1, 2500), new_dist=("uniform", 1, 4), n_sessions=12, n_blocks=2048)
     sess = W.make_sessions(cfg, 41)
     inputs = W.make_attn_inputs(cfg, sess, 41)
     got_dec, ref = check(oracle_mod, cfg, sess, inputs, label="decode kernel")
-    monkeypatch.setenv("SYMPH_ATTN_DECODE", "0")
-    got_main = gpu_attention(cfg, sess, inputs, scale=cfg.scale)
+    got_main = gpu_attention(cfg, sess, inputs, scale=cfg.scale, tuning=S.AttnTuning(decode=-1))
     max_abs, rel = attn_errors(got_main, ref)
     assert max_abs <= TOL[cfg.dtype][0] and rel <= TOL[cfg.dtype][1]
     d, _ = attn_errors(got_dec, widen(got_main).astype(np.float64))
     assert d <= 2e-2
 
 
+@pytest.mark.parametrize("decode", [1, -1])
+def test_more_sessions_than_one_scheduler_slice(oracle_mod, decode):
+    """9000 sessions with 0, 1 or 2 new tokens: the scheduler keeps 8192 sessions' unit offsets at a time, so the batch
+    runs as two slices on one stream and one workspace; through the decode kernel and through the work-item kernel."""
+    cfg = _cfg(n_sessions=9000, n_blocks=9000 * 3 + 8, prefix_dist=("uniform", 0, 40), new_dist=("uniform", 0, 2))
+    sess = W.make_sessions(cfg, 53)
+    assert sess.n_sessions > 8192 and sess.max_new_len * cfg.group <= 32
+    check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 53), label=f"9000 sessions, decode={decode}",
+          tuning=S.AttnTuning(decode=decode))
+
+
+@pytest.mark.parametrize("stated", [1, 2, 8])
+def test_understated_max_new_len_on_a_decode_shaped_batch(oracle_mod, stated):
+    """The caller says "no session has more than `stated` new tokens" (a decode step for the launcher), but some have up
+    to 40.  max_new_len only chooses kernels: the scheduler on the device sorts every session by its real length, the
+    long ones go through the work-item kernel that is launched beside the decode kernel, and every row is computed."""
+    cfg = _cfg(n_sessions=24, n_blocks=1024, prefix_dist=("uniform", 1, 700), new_dist=("uniform", 1, 3))
+    sess = W.make_sessions(cfg, 59)
+    new_lens = sess.new_lens.copy()
+    new_lens[[3, 11, 17]] = [40, 9, 33]          # beyond what one wave holds (G = 4: 8 tokens), and beyond `stated`
+    sess = W.make_sessions(cfg, 59, new_lens=new_lens)
+    assert sess.max_new_len == 40 and stated * cfg.group <= 32
+    check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, 59), label=f"max_new_len stated as {stated}",
+          max_new_len=stated)
+
+
 @pytest.mark.parametrize("seed", range(6))
-def test_seeded_random_batches(oracle_mod, monkeypatch, seed):
+def test_seeded_random_batches(oracle_mod, seed):
     """Five drawn batches per seed: kv-heads, group size, block size, session count, length ranges, and whether the
     batch is a decode step, a mix of short and long turns, or prefill turns only."""
     rng = np.random.default_rng(900 + seed)
@@ -144,9 +170,9 @@ def test_seeded_random_batches(oracle_mod, monkeypatch, seed):
         sess = W.make_sessions(cfg, case_seed)
         if sess.total_new_tokens == 0:
             continue
-        monkeypatch.setenv("SYMPH_ATTN_DECODE_WGS", str(int(rng.choice([8, 64, 512]))))
         check(oracle_mod, cfg, sess, W.make_attn_inputs(cfg, sess, case_seed),
-              label=f"{kind} S={n_sess} Hkv={hkv} G={g} bs={bs} pmax={pmax}")
+              label=f"{kind} S={n_sess} Hkv={hkv} G={g} bs={bs} pmax={pmax}",
+              tuning=S.AttnTuning(decode_wgs=int(rng.choice([8, 64, 512]))))
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])

@@ -90,12 +90,10 @@ def test_pack_unpack_edge_cases(oracle_mod, kw):
     run_case(oracle_mod, _cfg(**kw), seed=77)
 
 
-@pytest.mark.parametrize("mapping", ["0", "1"])
 @pytest.mark.parametrize("tokens", [1, 15, 16, 17, 31, 33, 47, 100])
-def test_workgroup_to_token_mappings(oracle_mod, monkeypatch, tokens, mapping):
-    """Identity and XCD-contiguous mapping of workgroups to the token space, forced for both directions, on the
+def test_workgroup_to_token_mappings(oracle_mod, tokens):
+    """The mappings of workgroups to the token space (XCD-contiguous for the gather, identity for the scatter) on the
     Llama row shape (2 KiB rows, two rows per workgroup), for workgroup counts below, at and between multiples of 8."""
-    monkeypatch.setenv("SYMPH_MIGRATE_XCD", mapping)
     run_case(oracle_mod, _cfg(n_kv_heads=8, head_dim=128, n_sessions=1, prefix_dist=("const", tokens), n_blocks=32),
              seed=tokens)
 

@@ -124,8 +124,9 @@ def _draw_lengths(dist, n, rng: np.random.Generator, block_size: int) -> np.ndar
     raise ValueError(f"unknown length distribution {kind!r}")
 
 
-def make_sessions(cfg: WorkloadConfig, seed: Optional[int] = None) -> SessionBatch:
+def make_sessions(cfg: WorkloadConfig, seed: Optional[int] = None, new_lens: Optional[np.ndarray] = None) -> SessionBatch:
     """Draw lengths, then hand every session consecutive slices of one seeded permutation of the pool.
+    ``new_lens``: new-turn lengths to use in place of the drawn ones (same draws otherwise).
 
     A session's blocks are therefore a uniform sample without replacement of the whole pool, listed in
     random order (fragmented); the destination table (the "fresh free list") takes the next slices of
@@ -135,6 +136,8 @@ def make_sessions(cfg: WorkloadConfig, seed: Optional[int] = None) -> SessionBat
     S, bs = cfg.n_sessions, cfg.block_size
     prefix = _draw_lengths(cfg.prefix_dist, S, rng, bs)
     new = _draw_lengths(cfg.new_dist, S, rng, bs)
+    if new_lens is not None:
+        new = np.asarray(new_lens, dtype=np.int32).reshape(S)
     nblk = (prefix.astype(np.int64) + bs - 1) // bs
     total_blk = int(nblk.sum())
     need = total_blk * (2 if cfg.fresh_tables else 1)
