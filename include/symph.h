@@ -215,6 +215,26 @@ int64_t symph_prefix_prefill_attn_workspace_bytes_tuned(const symph_kv_cache* ca
                                                         const symph_attn_tuning* tuning);
 
 /*
+ * symph_prefix_prefill_attn for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same kernels,
+ * same results up to the order in which partial results are combined; the scratch memory is a fixed array of 64 MiB
+ * inside the library's device code (one copy per GPU the library is used on, held until the process ends).  The
+ * call allocates nothing and frees nothing.  The first call on a device looks the array's address up once
+ * (hipGetSymbolAddress) - make that call outside a graph capture.  The work list is cut so that its partial results
+ * fit the array (fewer, longer pieces than the workspace version may choose); a batch whose list of query tiles alone
+ * needs more than the array (about a million query tiles) returns SYMPH_EWORKSPACE and nothing is launched.  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams) race and must be
+ * serialised by the caller; calls on one stream, or ordered by events, are fine, and nothing has to be cleared between
+ * them.
+ */
+int32_t symph_prefix_prefill_attn_static(const symph_kv_cache* cache, int32_t layer, const void* d_q,
+                                         const void* d_k_new, const void* d_v_new, void* d_out,
+                                         const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens,
+                                         const int32_t* d_block_table, int32_t table_stride, int32_t n_sessions,
+                                         int32_t n_q_heads, int32_t total_new_tokens, int32_t max_new_len,
+                                         int32_t max_prefix_len, float scale, void* stream);
+
+/*
  * What the device-side scheduler of the last attention call on `d_workspace` reported (a debugging aid like
  * symph_debug_check_tables: it copies one word to the host and synchronises `stream`).  *h_flags: bit 0 - a unit that
  * should have been split was left whole because the workspace has no room for its pieces (slower, still correct; it

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     kv_append,
     prefix_prefill_attn,
     prefix_prefill_attn_workspace_bytes,
+    prefix_prefill_attn_static,
     stage_to_host,
     stage_to_device,
     stage_layer_to_host,

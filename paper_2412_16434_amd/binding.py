@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = (
     "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
     "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_pack_units", "symph_kv_unpack_units", "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_prefix_prefill_attn_tuned",
-    "symph_prefix_prefill_attn_workspace_bytes_tuned", "symph_debug_attn_flags", "symph_stage_to_host",
+    "symph_prefix_prefill_attn_workspace_bytes_tuned", "symph_prefix_prefill_attn_static", "symph_debug_attn_flags", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
     "symph_mfma_reference", "symph_debug_check_tables",
     "symph_status_string",
@@ -98,6 +98,8 @@ def load_library():
     lib.symph_prefix_prefill_attn_tuned.argtypes = lib.symph_prefix_prefill_attn.argtypes + [tp]
     lib.symph_prefix_prefill_attn_workspace_bytes_tuned.restype = i64
     lib.symph_prefix_prefill_attn_workspace_bytes_tuned.argtypes = [cp, i32, i32, i32, i32, i32, tp]
+    lib.symph_prefix_prefill_attn_static.restype = i32
+    lib.symph_prefix_prefill_attn_static.argtypes = lib.symph_prefix_prefill_attn.argtypes[:16] + [vp]
     lib.symph_debug_attn_flags.restype = i32
     lib.symph_debug_attn_flags.argtypes = [vp, vp, C.POINTER(i32)]
     for fn in (lib.symph_stage_to_host, lib.symph_stage_to_device):
@@ -384,6 +386,16 @@ def prefix_prefill_attn(cache: KVCache, layer: int, q, k_new, v_new, out, cu_new
     else:
         _check(lib.symph_prefix_prefill_attn_tuned(C.byref(st), *args, C.byref(tuning)),
                "symph_prefix_prefill_attn_tuned")
+
+
+def prefix_prefill_attn_static(cache: KVCache, layer: int, q, k_new, v_new, out, cu_new_lens, prefix_lens, block_table,
+                               max_new_len: int, max_prefix_len: int, scale: float, stream=None) -> None:
+    """The same attention without a workspace argument: the library's fixed scratch array is used (nothing allocated)."""
+    st = cache.struct()
+    args = _attn_args(cache, layer, q, k_new, v_new, out, cu_new_lens, prefix_lens, block_table, max_new_len,
+                      max_prefix_len, scale)
+    _check(load_library().symph_prefix_prefill_attn_static(C.byref(st), *args, _stream_ptr(stream)),
+           "symph_prefix_prefill_attn_static")
 
 
 def debug_attn_flags(workspace, stream=None) -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsymph.so")
-SOURCES = ("api.hip", "kv_migrate.hip", "prefill_attn.hip", "kv_pool.cpp")  # the last one is host code only
+SOURCES = ("api.hip", "kv_migrate.hip", "prefill_attn.hip", "attn_static.hip", "kv_pool.cpp")  # the last one is host code only
 # packed-fp32 instructions are switched off for every device compile
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
                "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
