@@ -145,11 +145,13 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const GenericParams p)
 // pins each kv-head to one XCD (workgroups are dealt round-robin to the 8 XCDs), so the query tiles of a session
 // that re-read the same K,V share that XCD's L2.  Chunks of a split unit write unnormalised partial results
 // (running max, running sum, accumulators) to the workspace and a merge kernel combines them.
-struct WorkItem {   // 64 bytes
+struct WorkItem {   // 96 bytes
   int32_t s, t0, tile_begin, tile_end;
   int32_t pslot;                  // < 0: whole unit, the workgroup writes the output rows itself
   int32_t cu_s, n_new, n_prefix;  // of session s, so that a workgroup starts without looking them up
   int32_t merge, pslot0, n_chunks;  // chunk of a split unit: the unit's counter, its first slot, its number of chunks
+  int32_t first_ids[8];           // block ids of the eight 16-key groups of tiles tile_begin and tile_begin + 1: the
+                                  // workgroup's first K,V loads wait for this item only, not for a table read as well
   int32_t pad[5];
 };
 struct MergeItem {  // 16 bytes: a short turn that the decode kernel cut at the boundary of two shares
@@ -175,12 +177,14 @@ struct SchedParams {
   int32_t* hdr;
   WorkItem* items;
   int32_t* merge_cnt;   // [merges_bound][n_kv_heads]: chunks of a split unit that have written their partial result
+  const int32_t* table; // block table (may be null) and what is needed to find the ids of an item's first tiles
+  int32_t table_stride, log_bs;
 };
 
 constexpr int kBN = 64;  // keys per tile
 constexpr int kSchedThreads = 256;
 constexpr int kSchedBuckets = 64;      // one per lane of a wave: the bucket offsets are a single wave-level scan
-constexpr int kSchedMaxSessions = 8192;  // sessions whose unit offsets fit the scheduler's LDS table
+constexpr int kSchedMaxSessions = 4096;  // sessions whose lengths and unit offsets fit the scheduler's LDS tables
 
 __device__ __forceinline__ int unit_tiles(int P, int N, int t0, int bmt) {
   return (P + min(N, t0 + bmt) + kBN - 1) / kBN;
@@ -221,6 +225,7 @@ __device__ __forceinline__ void block_inclusive_scan2(int& a, int& b, int (*wave
 // left whole (flag bit 0), never dropped.
 __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const SchedParams p) {
   __shared__ int unit_off[kSchedMaxSessions + 1];
+  __shared__ int len_new[kSchedMaxSessions], len_prefix[kSchedMaxSessions], cu_of[kSchedMaxSessions];
   __shared__ int wave_sums[4][2];
   __shared__ unsigned long long total_tiles_s;
   __shared__ int hist[kSchedBuckets];
@@ -241,7 +246,15 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   int U = 0, n_dec = 0, dec_total = 0;
   for (int base = 0; base < S; base += kSchedThreads) {
     const int s = base + tid;
-    const int N = s < S ? p.cu_new_lens[s + 1] - p.cu_new_lens[s] : 0;
+    // the lengths are read from memory once and kept in LDS for the passes below
+    const int cu_s = s < S ? p.cu_new_lens[s] : 0;
+    const int N = s < S ? p.cu_new_lens[s + 1] - cu_s : 0;
+    const int P = s < S ? p.prefix_lens[s] : 0;
+    if (s < S) {
+      len_new[s] = N;
+      len_prefix[s] = P;
+      cu_of[s] = cu_s;
+    }
     int nq = N > 0 ? (N + p.bmt - 1) / p.bmt : 0, zero = 0, tot_q, tot_z;
     block_inclusive_scan2(nq, zero, wave_sums, tot_q, tot_z);
     if (s < S) unit_off[s] = U + nq - (N > 0 ? (N + p.bmt - 1) / p.bmt : 0);
@@ -250,7 +263,7 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
       // Short turns (1 <= N_s <= bmt_dec) are not cut into work items: the decode kernel splits the concatenation of
       // their key ranges evenly among its workgroups, and needs their indices and the prefix sum of their lengths.
       const int is_dec = N >= 1 && N <= p.bmt_dec;
-      const int nt = is_dec ? (p.prefix_lens[s] + N + 31) / 32 : 0;
+      const int nt = is_dec ? (P + N + 31) / 32 : 0;
       int ic = is_dec, itl = nt, tot_c, tot_t;
       block_inclusive_scan2(ic, itl, wave_sums, tot_c, tot_t);
       if (is_dec) {
@@ -287,8 +300,8 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     }
     r.s = lo;
     r.t0 = (u - unit_off[lo]) * p.bmt;
-    r.P = p.prefix_lens[lo];
-    r.N = p.cu_new_lens[lo + 1] - p.cu_new_lens[lo];
+    r.P = len_prefix[lo];
+    r.N = len_new[lo];
     r.nt = r.N <= p.bmt_dec ? 0 : unit_tiles(r.P, r.N, r.t0, p.bmt);
     return r;
   };
@@ -383,14 +396,21 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
         atomicMax(&n_pslot_s, c.pslot0 + c.n_real);
         atomicMax(&n_split_s, c.merge + 1);
       }
-      const int cu_s = p.cu_new_lens[c.u.s];
+      const int cu_s = cu_of[c.u.s];
+      const int32_t* table_row = p.table + (int64_t)c.u.s * p.table_stride;
       for (int ch = 0; ch < c.n_real; ++ch) {
         const int tb = ch * c.len, te = min(c.u.nt, tb + c.len);
         const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
-        if (pos < p.items_bound)
-          p.items[pos] = WorkItem{c.u.s, c.u.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, c.u.N, c.u.P,
-                                  c.merge, c.pslot0, c.n_real, {0, 0, 0, 0, 0}};
-        else
+        if (pos < p.items_bound) {
+          WorkItem w{c.u.s, c.u.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, c.u.N, c.u.P,
+                     c.merge, c.pslot0, c.n_real, {-1, -1, -1, -1, -1, -1, -1, -1}, {0, 0, 0, 0, 0}};
+          if (p.table && p.table_stride > 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)  // (index clamped to the row: an entry past the session's keys is never used)
+              w.first_ids[i] = table_row[min((tb * kBN + 16 * i) >> p.log_bs, p.table_stride - 1)];
+          }
+          p.items[pos] = w;
+        } else
           atomicOr(&flags_s, 2);  // more units than total_new_tokens and n_sessions allow: the lengths on the device
                                   // disagree with the host's bounds, and this piece of work is not done
       }
@@ -781,20 +801,23 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   f32x16 s_even[2], s_odd[2];  // scores of the even and of the odd tiles (counted from tile_begin)
   int ids_v[4];  // ids of the tile whose V rows are loaded next
   {
-    // the ids of the first two tiles with one load (lanes 0..7), before any K,V load is in flight
-    const int jb = (tile_begin * kBN + 16 * (lane & 7)) >> lb;
-    const int first8 = has_table ? table_row[min(jb, p.table_stride - 1)] : -1;
+    // the ids of the first two tiles came with the work item
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ids[i] = __builtin_amdgcn_readlane(first8, i);
+    for (int i = 0; i < 4; ++i) ids[i] = it.first_ids[i];
     issue_tile(k_bytes, p.k_new, K0, tile_begin);
     issue_tile(v_bytes, p.v_new, V0, tile_begin);
     if (tile_begin + 1 < tile_end) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) ids[i] = __builtin_amdgcn_readlane(first8, 4 + i);
+      for (int i = 0; i < 4; ++i) ids[i] = it.first_ids[4 + i];
       issue_tile(k_bytes, p.k_new, K1, tile_begin + 1);
     }
   }
-  wait_loads_and_sync();
+  // The first product needs K0 only: V0 and K1, issued after it, may still be on their way (loads return in order).
+  if (tile_begin + 1 < tile_end)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | 8);  // vmcnt(8)
+  else
+    __builtin_amdgcn_s_waitcnt(0x0F70 | 4);  // vmcnt(4)
+  __syncthreads();
   qk(K0, s_even);
 #pragma unroll
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
@@ -804,9 +827,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   mask(s_even, tile_begin);
   raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile
   softmax_exp_half(s_even[0], mb_cur, pb[0]);
-  // Every wave has read all of K0 for the first product before any wave overwrites it: the first iteration loads
-  // K(tile_begin + 2) into K0.  (Later iterations are ordered by the barrier at their end.)
-  __syncthreads();
+  // Every wave has read all of K0 for the first product before any wave overwrites it (the first iteration loads
+  // K(tile_begin + 2) into K0), and V0 and K1 have landed for all waves.  Later iterations end with the same pair.
+  wait_loads_and_sync();
 
   auto iteration = [&](const int j, auto par_c) {
     constexpr int PAR = decltype(par_c)::value;
@@ -905,29 +928,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     if (q_valid)
       store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + head) * kD, o_acc, 1.0f / l_tot, g2);
   } else {
-    // register dump, one float per thread per store: fully coalesced, and the merge kernel uses the same mapping
+    // Register dump, one float per thread per store: fully coalesced.  The chunks of a unit may run on different XCDs,
+    // whose L2 caches do not see each other's lines, so everything that passes between them is written and read at
+    // device scope (each access goes to the point where the XCDs agree) instead of flushing and invalidating whole
+    // caches around the hand-over: a release / acquire fence pair at device scope per chunk cost a quarter of the
+    // kernel's time on a batch that is all split units.
     float* part = p.partials + ((int64_t)it.pslot * Hkv + kvh) * kPartialFloats + tid;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) part[(dt * 16 + e) * 256] = o_acc[dt][e];
-    part[64 * 256] = m_run;
-    part[65 * 256] = l_run;
-    // The chunk that arrives last combines all of them (no further kernel): every thread makes its stores visible
-    // to the device, then one thread counts this chunk in.
-    __threadfence();
+      for (int e = 0; e < 16; ++e)
+        __hip_atomic_store(part + (dt * 16 + e) * 256, o_acc[dt][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(part + 64 * 256, m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(part + 65 * 256, l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The chunk that arrives last combines all of them (no further kernel).  Every wave waits until its stores have
+    // been performed, then one thread counts the chunk in.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
-    if (tid == 0) merges_here = atomicAdd(p.merge_cnt + (int64_t)it.merge * Hkv + kvh, 1) == it.n_chunks - 1;
+    if (tid == 0)
+      merges_here = __hip_atomic_fetch_add(p.merge_cnt + (int64_t)it.merge * Hkv + kvh, 1, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT) == it.n_chunks - 1;
     __syncthreads();
     if (!merges_here) return;
-    __threadfence();
     // out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being chunk c's softmax reference in log2
     // units (-inf: the chunk saw no key of the row).  All chunks are read back in chunk order, this one's too, so the
     // result does not depend on which chunk came last.  Same thread -> (row, d) mapping as the dump above.
     const float* first = p.partials + ((int64_t)it.pslot0 * Hkv + kvh) * kPartialFloats + tid;
     const int64_t chunk_stride = (int64_t)Hkv * kPartialFloats;
     float M = -INFINITY;
-    for (int ch = 0; ch < it.n_chunks; ++ch) M = fmaxf(M, first[ch * chunk_stride + 64 * 256]);
+    auto peer = [](const float* q) {  // a value another workgroup wrote during this launch
+      return __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    for (int ch = 0; ch < it.n_chunks; ++ch) M = fmaxf(M, peer(first + ch * chunk_stride + 64 * 256));
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -935,13 +968,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     float L = 0.f;
     for (int ch = 0; ch < it.n_chunks; ++ch) {
       const float* src = first + ch * chunk_stride;
-      const float mc = src[64 * 256];
+      const float mc = peer(src + 64 * 256);
       const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);
-      L += w * src[65 * 256];
+      L += w * peer(src + 65 * 256);
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o_acc[dt][e] = fmaf(w, src[(dt * 16 + e) * 256], o_acc[dt][e]);
+        for (int e = 0; e < 16; ++e) o_acc[dt][e] = fmaf(w, peer(src + (dt * 16 + e) * 256), o_acc[dt][e]);
     }
     const float l_tot = sum_across_halves(L);
     if (q_valid)
@@ -1518,6 +1551,9 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   sp.dec_off = (int32_t*)(ws + pl.off_dec_off);
   sp.items = (WorkItem*)(ws + pl.off_items);
   sp.merge_cnt = (int32_t*)(ws + pl.off_merge_cnt);
+  sp.table = a.table;
+  sp.table_stride = a.table_stride;
+  sp.log_bs = __builtin_ctz((unsigned)a.block_size);
 
   MfmaParams p;
   p.k_layer = (const __bf16*)a.k_layer;
@@ -1563,6 +1599,7 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
     p.cu_new_lens = sp.cu_new_lens;
     p.prefix_lens = sp.prefix_lens;
     p.table = a.table ? a.table + (int64_t)s0 * a.table_stride : nullptr;
+    sp.table = p.table;
     p.n_sessions = ns;
     hipLaunchKernelGGL(attn_schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, sp);
     // The work-item kernel runs for decode steps too.  Its list is then empty if max_new_len was a true bound; a

@@ -121,8 +121,8 @@ def test_decode_batch_agrees_with_the_work_item_path(oracle_mod):
 
 @pytest.mark.parametrize("decode", [1, -1])
 def test_more_sessions_than_one_scheduler_slice(oracle_mod, decode):
-    """9000 sessions with 0, 1 or 2 new tokens: the scheduler keeps 8192 sessions' unit offsets at a time, so the batch
-    runs as two slices on one stream and one workspace; through the decode kernel and through the work-item kernel."""
+    """9000 sessions with 0, 1 or 2 new tokens: the scheduler keeps 4096 sessions' lengths at a time, so the batch
+    runs as three slices on one stream and one workspace; through the decode kernel and through the work-item kernel."""
     cfg = _cfg(n_sessions=9000, n_blocks=9000 * 3 + 8, prefix_dist=("uniform", 0, 40), new_dist=("uniform", 0, 2))
     sess = W.make_sessions(cfg, 53)
     assert sess.n_sessions > 8192 and sess.max_new_len * cfg.group <= 32
