@@ -17,7 +17,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "symph_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# ORACLE_LIBRARY_PATH: load another build of the same source (the sanitizer job sets it in its child process)
+_LIB = os.environ.get("ORACLE_LIBRARY_PATH") or os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
@@ -42,6 +43,8 @@ def _load():
         lib.oracle_kv_buffer_bytes.argtypes = [i32, i32, i32, i32, i64]
         lib.oracle_kv_locate.restype = None
         lib.oracle_kv_locate.argtypes = [i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, vp, vp]
+        lib.oracle_kv_row_map.restype = None
+        lib.oracle_kv_row_map.argtypes = [i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp, vp]
         for fn in (lib.oracle_kv_pack, lib.oracle_kv_unpack):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp]
@@ -113,6 +116,22 @@ def kv_locate(layer_stride: int, block_stride: int, n_layers: int, block_size: i
     _load().oracle_kv_locate(layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim, _ptr(table),
                              table.shape[1], _ptr(prefix_lens), _ptr(offsets), s, l, kv, t, C.byref(pe), C.byref(be))
     return int(pe.value), int(be.value)
+
+
+def kv_row_map(layer_stride: int, block_stride: int, n_layers: int, block_size: int, n_kv_heads: int, head_dim: int,
+               table: np.ndarray, prefix_lens: np.ndarray, offsets: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """For every row of the migration buffer, in buffer order: (element offset of its source row inside its pool,
+    0 for K / 1 for V).  ``oracle_kv_locate`` for every (session, layer, K|V, token), as two arrays."""
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    S = prefix_lens.shape[0]
+    n_rows = int(offsets[S]) * 2 * n_layers
+    pool_elem = np.full(n_rows, -1, dtype=np.int64)
+    kv = np.full(n_rows, 255, dtype=np.uint8)
+    _load().oracle_kv_row_map(layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim, _ptr(table),
+                              table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(pool_elem), _ptr(kv))
+    return pool_elem, kv
 
 
 def kv_pack(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,

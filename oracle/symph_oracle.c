@@ -62,6 +62,28 @@ void oracle_kv_locate(int64_t layer_stride, int64_t block_stride, int32_t n_laye
   *buf_elem = (offsets[s] * 2 * n_layers + ((int64_t)2 * l + kv) * prefix_lens[s] + t) * row;
 }
 
+/* The whole index function written out as a table: for every row of the migration buffer, in buffer order, the
+ * element offset of the row it is a copy of inside its pool, and whether that pool is K (0) or V (1).  A loop over
+ * oracle_kv_locate and nothing else; it lets a checker that cannot hold the pools on the host (tens of GiB) compare
+ * every row of a buffer, or of a destination pool, against values that are a function of the pool offset.
+ * pool_elem_of_row, kv_of_row: offsets[n_sessions] * 2 * n_layers entries each. */
+void oracle_kv_row_map(int64_t layer_stride, int64_t block_stride, int32_t n_layers, int32_t block_size,
+                       int32_t n_kv_heads, int32_t head_dim, const int32_t* table, int32_t table_stride,
+                       const int32_t* prefix_lens, const int64_t* offsets, int32_t n_sessions,
+                       int64_t* pool_elem_of_row, uint8_t* kv_of_row) {
+  const int64_t row = (int64_t)n_kv_heads * head_dim;
+  for (int32_t s = 0; s < n_sessions; ++s)
+    for (int32_t l = 0; l < n_layers; ++l)
+      for (int32_t kv = 0; kv < 2; ++kv)
+        for (int32_t t = 0; t < prefix_lens[s]; ++t) {
+          int64_t pe, be;
+          oracle_kv_locate(layer_stride, block_stride, n_layers, block_size, n_kv_heads, head_dim, table,
+                           table_stride, prefix_lens, offsets, s, l, kv, t, &pe, &be);
+          pool_elem_of_row[be / row] = pe;
+          kv_of_row[be / row] = (uint8_t)kv;
+        }
+}
+
 /* Layers layer_begin .. layer_end-1 only: the buffer keeps the layout of the whole cache (Sec. 3.3 moves K,V layer by
  * layer; a layer of a session is one contiguous chunk of the layer-major buffer), everything else is not touched. */
 static int kv_copy(int to_buffer, void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride,
@@ -326,14 +348,14 @@ int oracle_prefix_prefill_attn(const void* k_base, const void* v_base, int64_t l
   const int64_t n_rows = token_subset ? n_subset : T;
   const int64_t layer_off = (int64_t)layer * layer_stride;
   int bad = 0;
-#pragma omp parallel for schedule(dynamic, 1)
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
   for (int64_t r = 0; r < n_rows * n_q_heads; ++r) {
     const int64_t tok = token_subset ? token_subset[r / n_q_heads] : r / n_q_heads;
     const int32_t h = (int32_t)(r % n_q_heads);
     int32_t s = 0;
     while (s < n_sessions && cu_new_lens[s + 1] <= tok) ++s;
     if (s >= n_sessions || tok < 0) {
-      bad = 1;
+      bad |= 1;
       continue;
     }
     const int32_t i = (int32_t)(tok - cu_new_lens[s]);

@@ -234,9 +234,13 @@ def test_mfma_reference_counts_its_work_and_leaves_the_sink_alone():
 
 
 # ---------------------------------------------------------------------------------------------------------
-# full sizes: counter-filled device pools, sampled rows against the oracle's index map, whole-pool properties
+# full sizes: counter-filled device pools, EVERY row of the buffer and of the destination blocks against the oracle's
+# index function, whole-pool properties for everything else
 # ---------------------------------------------------------------------------------------------------------
-def _full_size_case(oracle_mod, cfg, n_sample=20000):
+ROWS_PER_SLICE = 1 << 15
+
+
+def _full_size_case(oracle_mod, cfg):
     sess = W.make_sessions(cfg)
     L, nb, bs = cfg.n_layers, cfg.n_blocks, cfg.block_size
     shape = (L, nb, bs, cfg.n_kv_heads, cfg.head_dim)
@@ -253,42 +257,51 @@ def _full_size_case(oracle_mod, cfg, n_sample=20000):
     torch.cuda.synchronize()
     assert buf.numel() * 2 == sess.payload_bytes()
 
-    # (1) sampled rows: the oracle's index map says where a row comes from and where it goes
-    rng = np.random.default_rng(5)
+    # The oracle's index function for every row of the buffer (source table, destination table).  A pool element holds
+    # counter(seed, K|V, its own element offset), so the expected bits of a buffer row follow from the offset of the
+    # row it is a copy of, and a row of a destination block must hold what its buffer row holds.
     row = cfg.row_elems
-    ss = rng.integers(0, sess.n_sessions, n_sample)
-    ts = (rng.random(n_sample) * sess.prefix_lens[ss]).astype(np.int64)
-    ts[: sess.n_sessions] = sess.prefix_lens - 1                 # every session's last token (partial block)
-    ss[: sess.n_sessions] = np.arange(sess.n_sessions)
-    ls = rng.integers(0, L, n_sample)
-    kvs = rng.integers(0, 2, n_sample)
-    pe = np.empty(n_sample, np.int64); be = np.empty(n_sample, np.int64)
-    pe_dst = np.empty(n_sample, np.int64)
-    for i in range(n_sample):
-        pe[i], be[i] = oracle_mod.kv_locate(cfg.layer_elems, cfg.block_elems, L, bs, cfg.n_kv_heads, cfg.head_dim,
-                                            sess.block_table, sess.prefix_lens, sess.buf_token_offsets,
-                                            int(ss[i]), int(ls[i]), int(kvs[i]), int(ts[i]))
-        pe_dst[i], _ = oracle_mod.kv_locate(cfg.layer_elems, cfg.block_elems, L, bs, cfg.n_kv_heads, cfg.head_dim,
-                                            sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets,
-                                            int(ss[i]), int(ls[i]), int(kvs[i]), int(ts[i]))
-    cols = np.arange(row, dtype=np.int64)
-    expect = np.where(kvs[:, None] == 0, W.counter_bits_host(cfg.seed, 0, pe[:, None] + cols),
-                      W.counter_bits_host(cfg.seed, 1, pe[:, None] + cols))
-    idx = torch.from_numpy(be[:, None] + cols).to(DEV)
-    got = buf.view(torch.int16)[idx].cpu().numpy().view(np.uint16)
-    assert np.array_equal(got, expect), "pack: sampled rows differ"
+    geo = (cfg.layer_elems, cfg.block_elems, L, bs, cfg.n_kv_heads, cfg.head_dim)
+    pe_src, kv = oracle_mod.kv_row_map(*geo, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    pe_dst, kv2 = oracle_mod.kv_row_map(*geo, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets)
+    n_rows = pe_src.size
+    assert n_rows * row == buf.numel() and np.array_equal(kv, kv2) and pe_src.min() >= 0 and pe_dst.min() >= 0
+    cols = torch.arange(row, dtype=torch.int64, device=DEV)
+    buf_rows = buf.view(torch.int16).view(n_rows, row)
+    pools_flat = (k_pool.view(torch.int16).view(-1), v_pool.view(torch.int16).view(-1))
 
-    # (2) unpack into the fresh destination blocks of the same pool
+    def for_every_row(check):
+        """check(slice of rows, salt, source offsets, destination offsets, expected bits [n][row]) over the whole buffer."""
+        for r0 in range(0, n_rows, ROWS_PER_SLICE):
+            r1 = min(n_rows, r0 + ROWS_PER_SLICE)
+            for salt in (0, 1):
+                pick = np.nonzero(kv[r0:r1] == salt)[0]
+                if pick.size == 0:
+                    continue
+                rows = torch.from_numpy(pick + r0).to(DEV)
+                src = torch.from_numpy(pe_src[r0:r1][pick]).to(DEV)
+                dst = torch.from_numpy(pe_dst[r0:r1][pick]).to(DEV)
+                expect = W.counter_bits_device(cfg.seed, salt, src[:, None] + cols[None, :])
+                check(rows, salt, src, dst, expect)
+
+    # (1) pack: every row of the buffer
+    def check_pack(rows, salt, src, dst, expect):
+        assert torch.equal(buf_rows[rows], expect), "pack: a buffer row differs from the row the oracle names"
+    for_every_row(check_pack)
+
+    # (2) unpack into the fresh destination blocks of the same pool: every destination row holds its buffer row, and
+    #     every source row still holds what it held
     gpu_unpack(cache, ds, buf, dst=True)
     torch.cuda.synchronize()
-    kflat, vflat = k_pool.view(torch.int16).view(-1), v_pool.view(torch.int16).view(-1)
-    idx = torch.from_numpy(pe_dst[:, None] + cols).to(DEV)
-    got_k = kflat[idx].cpu().numpy().view(np.uint16)
-    got_v = vflat[idx].cpu().numpy().view(np.uint16)
-    assert np.array_equal(np.where(kvs[:, None] == 0, got_k, got_v), expect), "unpack: sampled rows differ"
+
+    def check_unpack(rows, salt, src, dst, expect):
+        flat = pools_flat[salt]
+        assert torch.equal(flat[dst[:, None] + cols[None, :]], expect), "unpack: a destination row differs"
+        assert torch.equal(flat[src[:, None] + cols[None, :]], expect), "unpack: a source row changed"
+    for_every_row(check_unpack)
 
     # (3) whole pool: exactly the source and destination blocks hold data, everything else is still sentinel,
-    #     and the unused tail slots of every destination last block are still sentinel
+    #     and the unused tail slots of every source and destination last block are still sentinel
     dst_blocks = sess.owned_blocks(dst=True)
     owned = np.zeros(nb, dtype=bool)
     owned[src_blocks] = True
@@ -310,6 +323,8 @@ def _full_size_case(oracle_mod, cfg, n_sample=20000):
     again = gpu_pack(cache, ds, dst=True)
     torch.cuda.synchronize()
     assert torch.equal(again.view(torch.int16), buf.view(torch.int16))
+    print(f"[migrate parity] {cfg.name}: {n_rows} buffer rows and {n_rows} destination rows of {row} elements compared, "
+          f"{L * nb * 2} pool blocks scanned", flush=True)
 
 
 @pytest.mark.parametrize("name", ["llama8b", "llama70b_long", "many_short", "mixed_resume_incoming"])

@@ -176,6 +176,32 @@ def test_locate_against_tagged_pool(oracle_mod):
                                                           t % cfg.block_size, 0, 0)
 
 
+def test_row_map_against_tagged_pool(oracle_mod):
+    """The table form of the index function (what the full-size GPU parity tests compare whole buffers with): walk
+    the buffer in order, state from the layout rules alone which (K|V, layer, block, slot) each row is, and require
+    the map to name exactly that row of the tagged pool; every row is named, none twice."""
+    cfg = small_cfg("fp32", n_sessions=5, n_layers=3, prefix_dist=("uniform", 0, 23))
+    sess = W.make_sessions(cfg, 6)
+    k_pool, v_pool = tagged_pools(cfg)
+    pool_elem, kv = oracle_mod.kv_row_map(cfg.layer_elems, cfg.block_elems, cfg.n_layers, cfg.block_size,
+                                          cfg.n_kv_heads, cfg.head_dim, sess.block_table, sess.prefix_lens,
+                                          sess.buf_token_offsets)
+    assert pool_elem.size == sess.total_prefix_tokens * 2 * cfg.n_layers and pool_elem.min() >= 0 and kv.max() <= 1
+    r = 0
+    for s in range(sess.n_sessions):
+        for layer in range(cfg.n_layers):
+            for which in (0, 1):
+                for tok in range(int(sess.prefix_lens[s])):
+                    pool = (v_pool if which else k_pool).ravel()
+                    kvd, l, b, o, g, c = decode_tag(pool[pool_elem[r]: pool_elem[r] + 1].view(np.uint32), cfg)
+                    assert kv[r] == which
+                    assert (kvd[0], l[0], b[0], o[0], g[0], c[0]) == (
+                        which, layer, sess.block_table[s, tok // cfg.block_size], tok % cfg.block_size, 0, 0)
+                    r += 1
+    assert r == pool_elem.size
+    assert np.unique(pool_elem * 2 + kv).size == pool_elem.size      # (no block is shared in this batch)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_unpack_round_trips_and_leaves_other_bytes_alone(oracle_mod, dtype):
     cfg = small_cfg(dtype, n_sessions=6, n_layers=2, n_blocks=96, prefix_dist=("geometric", 9.0, 1, 29))
