@@ -24,9 +24,26 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the readings of the plain
-# copy kernel of known size (profiles/bench_llama8b_hbm_traffic.md); other workloads have not been measured.
-MEASURED_TRAFFIC_BYTES = {"llama8b": {"kv_migrate": 17.22e9, "attn": 3.92e8}}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic(workload: str) -> dict:
+    """HBM bytes per launch from profiles/bench_<workload>_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    scaled by the readings of the plain copy kernel of known size; written by `bench.py --write-traffic-summary`):
+    the line `traffic_bytes_per_launch: kernel=bytes ...`.  Empty if that workload has not been profiled."""
+    path = os.path.join(PROFILES, f"bench_{workload}_hbm_traffic.md")
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    for item in line.split(":", 1)[1].split():
+                        k, v = item.split("=")
+                        out[k] = float(v)
+    except OSError:
+        pass
+    return out
+
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
@@ -46,6 +63,11 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staging", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the CPU-baseline leg")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="leave out the other four workloads, the mixed-resume modes and the decode step")
+    ap.add_argument("--write-traffic-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no GPU work: read the counter csv files of two `rocprofv3 --pmc FETCH_SIZE` / `--pmc "
+                         "WRITE_SIZE` runs of this script and write profiles/bench_<config>_hbm_traffic.md")
     return ap.parse_args()
 
 
@@ -66,17 +88,20 @@ def cpu_baseline(cfg, sess, budget_s: float):
     import workloads as W
     oracle.build()
     threads = oracle.num_threads()
-    # migration sample: same shapes and length recipe, fewer layers and sessions, small pool
-    mcfg = W.scaled_config(cfg, n_layers=min(cfg.n_layers, 4), n_sessions=min(cfg.n_sessions, 4), n_blocks=4096)
+    # migration sample: same shapes, lengths and sessions, fewer layers, small pool: a payload of more than 2 GB, far
+    # beyond the host's last-level cache, so that the rate is a DRAM figure
+    import dataclasses
+    mcfg = dataclasses.replace(W.scaled_config(cfg, n_layers=min(cfg.n_layers, 8), n_blocks=max(8192, cfg.n_blocks // 8)),
+                               fresh_tables=False)      # (the scatter goes back through the source table)
     msess = W.make_sessions(mcfg)
     shape = (mcfg.n_layers, mcfg.n_blocks, mcfg.block_size, mcfg.n_kv_heads, mcfg.head_dim)
     dt = np.uint16 if cfg.dtype == "bf16" else np.float32
-    kp = np.arange(int(np.prod(shape)), dtype=np.uint32).astype(dt).reshape(shape)
-    vp = kp[::-1].copy()
+    kp = np.resize(np.arange(65521, dtype=np.uint32).astype(dt), shape)      # (values do not matter to a copy)
+    vp = np.resize(np.arange(65519, dtype=np.uint32).astype(dt), shape)
     t0 = time.perf_counter()
     buf = oracle.kv_pack(kp, vp, msess.block_table, msess.prefix_lens, msess.buf_token_offsets)
     t1 = time.perf_counter()
-    oracle.kv_unpack(kp, vp, msess.dst_block_table, msess.prefix_lens, msess.buf_token_offsets, buf)
+    oracle.kv_unpack(kp, vp, msess.block_table, msess.prefix_lens, msess.buf_token_offsets, buf)
     t2 = time.perf_counter()
     mig_bytes = 2.0 * msess.payload_bytes()          # read + write
     pack_gbs = mig_bytes / (t1 - t0) / 1e9
@@ -108,7 +133,7 @@ def cpu_baseline(cfg, sess, budget_s: float):
     return {
         "value": step_bytes / step_s / 1e9, "unit": "GB/s", "cores": threads, "cpu_model": _cpu_model(), "kind": "oracle",
         "sample": (f"pack+unpack of {msess.n_sessions} sessions x {mcfg.n_layers} layers "
-                   f"({msess.payload_bytes() / 1e6:.0f} MB payload, same shapes and length recipe); attention on "
+                   f"({msess.payload_bytes() / 1e6:.0f} MB payload, same shapes and lengths); attention on "
                    f"{n_rows} of {T} query tokens of the real batch (all heads); step extrapolated from the three rates"),
         "pack_GBps": pack_gbs, "unpack_GBps": unpack_gbs, "attn_fp64_GFLOPs": attn_gflops,
         "extrapolated_step_ms": step_s * 1e3,
@@ -121,10 +146,8 @@ def attn_only(args, cfg, sess):
     import paper_2412_16434_amd as S
     import workloads as W
     dev = "cuda:0"
-    kh, vh, qh, knh, vnh = W.make_attn_inputs(cfg, sess)
-    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
-    cache = S.KVCache(to_dev(kh)[None], to_dev(vh)[None])
-    q, k_new, v_new = to_dev(qh), to_dev(knh), to_dev(vnh)
+    kp, vp, q, k_new, v_new = W.make_attn_inputs_device(cfg, sess, dev)
+    cache = S.KVCache(kp[None], vp[None])
     out = torch.empty_like(q)
     table = torch.from_numpy(sess.block_table).to(dev)
     prefix_lens = torch.from_numpy(sess.prefix_lens).to(dev)
@@ -172,13 +195,12 @@ def decode_step(args):
     dev = "cuda:0"
     cfg = W.get_config("mixed_resume")
     sess = W.make_sessions(cfg)
-    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
-    kh, vh, qh, knh, vnh = W.make_attn_inputs(cfg, sess)
-    cache = S.KVCache(to_dev(kh)[None], to_dev(vh)[None])
+    kp, vp, q_all, kn_all, vn_all = W.make_attn_inputs_device(cfg, sess, dev)
+    cache = S.KVCache(kp[None], vp[None])
     new_lens = np.diff(sess.cu_new_lens)
     idx = np.nonzero(new_lens == 1)[0]
-    rows = sess.cu_new_lens[:-1][idx]                      # the one query row of each such session
-    q, k_new, v_new = (to_dev(np.ascontiguousarray(a[rows])) for a in (qh, knh, vnh))
+    rows = torch.from_numpy(sess.cu_new_lens[:-1][idx].astype(np.int64)).to(dev)   # the one query row of each such session
+    q, k_new, v_new = (a[rows].contiguous() for a in (q_all, kn_all, vn_all))
     out = torch.empty_like(q)
     n = len(idx)
     prefix_h = np.ascontiguousarray(sess.prefix_lens[idx])
@@ -209,7 +231,7 @@ def decode_step(args):
     main_ms, main_out = timed(S.AttnTuning(decode=-1))   # (needs no more workspace than the default plan)
     diff = float((dec_out.float() - main_out.float()).abs().max())
     gbs = kv_bytes / dec_ms / 1e6
-    print(json.dumps({
+    return ({
         "metric": "decode step: K,V GB/s of prefix-prefill attention on one-token rows, as % of HBM peak",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dec_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -220,7 +242,7 @@ def decode_step(args):
                              "pct_hbm_peak": 100 * kv_bytes / main_ms / 1e6 / HBM_PEAK_GBS},
         "max_abs_difference_between_the_two": diff,
         "roofline": {"kernel": "attn_decode", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None}}))
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None}})
 
 
 def resume_mix(args):
@@ -233,10 +255,8 @@ def resume_mix(args):
     dev = "cuda:0"
     acfg, ucfg = W.get_config("mixed_resume"), W.get_config("mixed_resume_incoming")
     asess, usess = W.make_sessions(acfg), W.make_sessions(ucfg)
-    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
-    kh, vh, qh, knh, vnh = W.make_attn_inputs(acfg, asess)
-    acache = S.KVCache(to_dev(kh)[None], to_dev(vh)[None])
-    q, k_new, v_new = to_dev(qh), to_dev(knh), to_dev(vnh)
+    kp, vp, q, k_new, v_new = W.make_attn_inputs_device(acfg, asess, dev)
+    acache = S.KVCache(kp[None], vp[None])
     out = torch.empty_like(q)
     atable = torch.from_numpy(asess.block_table).to(dev)
     aprefix = torch.from_numpy(asess.prefix_lens).to(dev)
@@ -279,7 +299,7 @@ def resume_mix(args):
     torch.cuda.synchronize()
     attn_ms, unpack_ms, both_ms = timed([attn]), timed([unpack]), timed([attn, unpack])
     tflops = asess.attn_flops() / attn_ms / 1e9
-    print(json.dumps({
+    return ({
         "metric": "mixed resume: prefix-prefill attn beside kv_unpack on a second stream", "value": both_ms, "unit": "ms",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": both_ms, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -290,7 +310,7 @@ def resume_mix(args):
                        "kv_GBps": asess.attn_bytes() / attn_ms / 1e6},
         "unpack_alone": {"ms": unpack_ms, "GBps": 2.0 * payload / unpack_ms / 1e6,
                          "pct_hbm_peak": 100 * 2.0 * payload / unpack_ms / 1e6 / HBM_PEAK_GBS},
-        "both": {"ms": both_ms, "sum_of_alone_ms": attn_ms + unpack_ms, "max_of_alone_ms": max(attn_ms, unpack_ms)}}))
+        "both": {"ms": both_ms, "sum_of_alone_ms": attn_ms + unpack_ms, "max_of_alone_ms": max(attn_ms, unpack_ms)}})
 
 
 def pipelined_resume(args, cfg, sess):
@@ -431,8 +451,176 @@ def pipelined_resume(args, cfg, sess):
                        "new_tokens_only_ms": wb_tail_ms, "new_tokens_payload_bytes": tail_payload}}))
 
 
+def _median_event_ms(fn, warmup: int, iters: int) -> float:
+    """Median time of `fn` (one library call on the current stream), events around each of `iters` calls issued back
+    to back, one synchronisation at the end."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    return float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+
+
+def _attn_figures(sess, ms: float) -> dict:
+    """TFLOP/s against the matrix-core peak, K,V GB/s against the HBM peak, and which of the two roofs lies lower for
+    this batch (the time each would need at its peak)."""
+    flops, nbytes = sess.attn_flops(), sess.attn_bytes()
+    tflops, gbs = flops / ms / 1e9, nbytes / ms / 1e6
+    t_mfma, t_hbm = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    return {"ms": ms, "TFLOPs": tflops, "frac_mfma_bf16_peak": tflops / MFMA_BF16_PEAK_TFLOPS, "kv_GBps": gbs,
+            "frac_hbm_peak": gbs / HBM_PEAK_GBS, "flops": flops, "bytes": nbytes,
+            "flop_per_byte": flops / max(nbytes, 1), "binding_roof": "mfma" if t_mfma >= t_hbm else "hbm"}
+
+
+def measure_config(args, name: str) -> dict:
+    """pack, unpack (all layers, every session) and one-layer attention of one workload, each timed on its own with
+    events on the launch stream.  Pools hold zeros for the migration legs (a copy does not look at values); the
+    attention inputs are drawn on the device with the workload's shapes, lengths, tables and value distribution."""
+    import torch
+    import paper_2412_16434_amd as S
+    import workloads as W
+    dev = "cuda:0"
+    cfg = W.get_config(name)
+    mig_cfg = W.get_config("mixed_resume_incoming") if name == "mixed_resume" else cfg     # (the sessions that arrive)
+    out = {"workload": name, "dtype": cfg.dtype}
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+    # ---- migration legs
+    msess = W.make_sessions(mig_cfg)
+    shape = (mig_cfg.n_layers, mig_cfg.n_blocks, mig_cfg.block_size, mig_cfg.n_kv_heads, mig_cfg.head_dim)
+    cache = S.KVCache(torch.zeros(shape, dtype=tdt, device=dev), torch.zeros(shape, dtype=tdt, device=dev))
+    table = torch.from_numpy(msess.block_table).to(dev)
+    dst_table = torch.from_numpy(msess.dst_block_table).to(dev)
+    plens = torch.from_numpy(msess.prefix_lens).to(dev)
+    offs = torch.from_numpy(msess.buf_token_offsets).to(dev)
+    total = msess.total_prefix_tokens
+    payload = S.kv_buffer_bytes(cache, total)
+    buf = torch.zeros(max(payload // cache.k_pool.element_size(), 8), dtype=tdt, device=dev)
+    # pack then unpack, alternating as in the step, events around each call
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(7)]
+    for it in range(-2, 7):
+        if it >= 0: evs[it][0].record()
+        S.kv_pack(cache, table, plens, offs, total, buf)
+        if it >= 0: evs[it][1].record()
+        S.kv_unpack(cache, dst_table, plens, offs, total, buf)
+        if it >= 0: evs[it][2].record()
+    torch.cuda.synchronize()
+    pack_ms = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
+    unpack_ms = float(np.median([e[1].elapsed_time(e[2]) for e in evs]))
+    for leg, ms in (("kv_pack", pack_ms), ("kv_unpack", unpack_ms)):
+        gbs = 2.0 * payload / ms / 1e6
+        out[leg] = {"ms": ms, "GBps": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS, "payload_bytes": payload,
+                    "sessions": msess.n_sessions, "layers": mig_cfg.n_layers}
+        if 2 * payload < (256 << 20):
+            out[leg]["note"] = "payload lives in the caches: no share-of-peak claim"
+    del cache, buf, table, dst_table
+    torch.cuda.empty_cache()
+
+    # ---- attention on one layer
+    sess = W.make_sessions(cfg)
+    if cfg.dtype == "bf16":
+        k_pool, v_pool, q, k_new, v_new = W.make_attn_inputs_device(cfg, sess, dev)
+    else:
+        k_pool, v_pool, q, k_new, v_new = (torch.from_numpy(a).to(dev) for a in W.make_attn_inputs(cfg, sess))
+        k_pool.nan_to_num_(0.0); v_pool.nan_to_num_(0.0)
+    acache = S.KVCache(k_pool[None], v_pool[None])
+    o = torch.empty_like(q)
+    atable = torch.from_numpy(sess.block_table).to(dev)
+    aplens = torch.from_numpy(sess.prefix_lens).to(dev)
+    cu = torch.from_numpy(sess.cu_new_lens).to(dev)
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(acache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
+                                                     sess.max_new_len, sess.max_prefix_len)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    attn_ms = _median_event_ms(
+        lambda: S.prefix_prefill_attn(acache, 0, q, k_new, v_new, o, cu, aplens, atable, sess.max_new_len,
+                                      sess.max_prefix_len, cfg.scale, workspace=ws if ws_bytes else None), 3, 15)
+    out["prefix_prefill_attn"] = {**_attn_figures(sess, attn_ms), "sessions": sess.n_sessions,
+                                  "new_tokens": sess.total_new_tokens, "prefix_tokens": sess.total_prefix_tokens}
+    if cfg.dtype != "bf16":
+        out["prefix_prefill_attn"]["note"] = "fp32 runs the plain one-wave-per-row kernel: correctness path, no roofline claim"
+    del acache, k_pool, v_pool, ws
+    torch.cuda.empty_cache()
+    return out
+
+
+def write_traffic_summary(args):
+    """profiles/bench_<config>_hbm_traffic.md from the counter csv files of two rocprofv3 runs of this script (one with
+    --pmc FETCH_SIZE, one with --pmc WRITE_SIZE).  The plain copy kernel of known size in the same runs gives the unit
+    of each counter on this machine; every other kernel's readings are scaled by it."""
+    import csv
+    import glob
+    import workloads as W
+    cfg = W.get_config(args.config)
+    sess = W.make_sessions(cfg)
+    payload = sess.payload_bytes()
+
+    def means(d, counter):
+        acc = {}
+        for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            with open(f) as fh:
+                for r in csv.DictReader(fh):
+                    if r.get("Counter_Name") == counter:
+                        acc.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+        return {k: (sum(v) / len(v), len(v)) for k, v in acc.items()}
+    fetch, write = means(args.write_traffic_summary[0], "FETCH_SIZE"), means(args.write_traffic_summary[1], "WRITE_SIZE")
+
+    def pick(table, *subs):
+        hits = [(k, v) for k, v in table.items() if all(s in k for s in subs)]
+        if not hits:
+            raise SystemExit(f"no kernel matching {subs} in the counter files")
+        n = sum(v[1] for _, v in hits)
+        return sum(v[0] * v[1] for _, v in hits) / n, n
+    copy_f, _ = pick(fetch, "device_copy_kernel")
+    copy_w, _ = pick(write, "device_copy_kernel")
+    unit_f, unit_w = payload / copy_f, payload / copy_w          # bytes per count
+    rows, line = [], []
+    for label, key, subs, algo in (
+            ("kv_pack", "kv_pack", ("kv_migrate_kernel", "true, 1,"), 2.0 * payload),
+            ("kv_unpack", "kv_unpack", ("kv_migrate_kernel", "false, 2,"), 2.0 * payload),
+            ("prefix_prefill_attn (main kernel)", "attn_mfma", ("attn_mfma_kernel",), float(sess.attn_bytes()))):
+        f, nf = pick(fetch, *subs)
+        w, nw = pick(write, *subs)
+        rd, wr = f * unit_f, w * unit_w
+        rows.append(f"| {label} | {f:.4g} ({nf}) | {w:.4g} ({nw}) | {rd / 1e9:.3f} GB | {wr / 1e9:.3f} GB | "
+                    f"{(rd + wr) / 1e9:.3f} GB | {algo / 1e9:.3f} GB | {(rd + wr) / algo:.3f} |")
+        line.append(f"{key}={rd + wr:.6g}")
+    text = f"""# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: HBM traffic per launch, workload {cfg.name}, one MI355X
+
+Commands (separate runs, from the repo root on the GPU box; the third needs no GPU):
+
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o f -- python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-staging --no-per-config
+    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -o w -- python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-staging --no-per-config
+    python3 bench.py --write-traffic-summary gpurun_out/pmc_fetch gpurun_out/pmc_write
+
+Calibration: the plain copy kernel (`symph_device_copy`) of the same runs reads {payload} B and writes {payload} B; its
+mean FETCH_SIZE is {copy_f:.5g} and its mean WRITE_SIZE {copy_w:.5g}, so one count is {unit_f:.1f} B of reads and
+{unit_w:.1f} B of writes on this machine.
+
+| kernel | FETCH_SIZE, mean (launches) | WRITE_SIZE, mean (launches) | HBM read | HBM written | total | algorithmic bytes | total / algorithmic |
+|---|---|---|---|---|---|---|---|
+""" + "\n".join(rows) + f"""
+
+Algorithmic bytes: pack / unpack 2 x payload (every byte read once and written once); attention: K,V of one layer once,
+Q, O, K_new, V_new.  bench.py reads the next line for `roofline.traffic`:
+
+traffic_bytes_per_launch: {' '.join(line)}
+"""
+    path = os.path.join(PROFILES, f"bench_{cfg.name}_hbm_traffic.md")
+    with open(path, "w") as f:
+        f.write(text)
+    print(path)
+
+
 def main():
     args = parse_args()
+    if args.write_traffic_summary:
+        write_traffic_summary(args)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (sessions shard across GPUs with no exchange step; "
               "no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
@@ -448,10 +636,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.only == "resume":
-        resume_mix(args)
+        print(json.dumps(resume_mix(args)))
         return
     if args.only == "decode":
-        decode_step(args)
+        print(json.dumps(decode_step(args)))
         return
     cfg = W.get_config(args.config)
     if cfg.dtype != "bf16":
@@ -676,6 +864,7 @@ def main():
         staging = res
         del host
 
+    traffic = measured_traffic(cfg.name)
     mig_bytes = 2.0 * payload                 # every payload byte read once and written once
     attn_flops = sess.attn_flops()
     attn_bytes = sess.attn_bytes()
@@ -717,11 +906,31 @@ def main():
         "host_staging": staging,
         "roofline": {"kernel": f"kv_migrate ({dominant})", "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("kv_migrate")},
+                     "traffic": traffic.get("kv_pack" if dominant == "pack" else "kv_unpack")},
         "roofline_attn": {"kernel": "attn_mfma", "bound": "mfma", "achieved": attn_tflops,
                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                          "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("attn")},
+                          "traffic": traffic.get("attn_mfma")},
     }
+    if not args.no_per_config:
+        # the other workloads, each leg timed on its own; the headline workload's row repeats the step's figures
+        del k_pool, v_pool, pool, cache, slot_pool, buf, tail_buf
+        torch.cuda.empty_cache()
+        per = {cfg.name: {"workload": cfg.name, "dtype": cfg.dtype, "measured": "inside the timed step",
+                          "kv_pack": {"ms": pack_ms, "GBps": pack_gbs, "frac_hbm_peak": pack_gbs / HBM_PEAK_GBS,
+                                      "payload_bytes": payload},
+                          "kv_unpack": {"ms": unpack_ms, "GBps": unpack_gbs, "frac_hbm_peak": unpack_gbs / HBM_PEAK_GBS,
+                                        "payload_bytes": payload},
+                          "prefix_prefill_attn": _attn_figures(sess, attn_ms)}}
+        for name in ("tiny_fp32", "llama70b_long", "many_short", "mixed_resume"):
+            if name != cfg.name:
+                per[name] = measure_config(args, name)
+        result["per_config"] = per
+        mix = resume_mix(args)
+        result["mixed_resume"] = {k: mix[k] for k in ("attn_alone", "unpack_alone", "both")}
+        dec = decode_step(args)
+        result["decode_step"] = {"config": dec["config"], "decode_kernel": dec["decode_kernel"],
+                                 "work_item_kernel": dec["work_item_kernel"],
+                                 "max_abs_difference_between_the_two": dec["max_abs_difference_between_the_two"]}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, sess, args.cpu_seconds)
     print(json.dumps(result))

@@ -22,6 +22,7 @@ from .values import (
     counter_bits_host,
     counter_bits_device,
     make_attn_inputs,
+    make_attn_inputs_device,
     make_pool_host,
     fill_pool_blocks_device,
     SENTINEL16,
@@ -31,5 +32,5 @@ __all__ = [
     "WorkloadConfig", "CONFIGS", "get_config", "scaled_config",
     "SessionBatch", "UnitBatch", "make_sessions", "make_units",
     "f32_to_bf16_bits", "bf16_bits_to_f32", "counter_bits_host", "counter_bits_device",
-    "make_attn_inputs", "make_pool_host", "fill_pool_blocks_device", "SENTINEL16",
+    "make_attn_inputs", "make_attn_inputs_device", "make_pool_host", "fill_pool_blocks_device", "SENTINEL16",
 ]

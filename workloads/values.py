@@ -174,3 +174,28 @@ def fill_pool_blocks_device(k_pool, v_pool, cfg: WorkloadConfig, blocks: np.ndar
                 b = blocks_t[c0: c0 + per_chunk]
                 idx = ((layer * cfg.n_blocks + b) * be)[:, None] + within[None, :]
                 flat[layer].index_copy_(0, b, counter_bits_device(seed, salt, idx))
+
+
+def make_attn_inputs_device(cfg: WorkloadConfig, sess: SessionBatch, device, seed: Optional[int] = None):
+    """The inputs of one attention layer drawn ON the device, for timing runs whose pools are too large to draw on the
+    host in reasonable time: (k_pool, v_pool, q, k_new, v_new) as torch bf16 tensors of the shapes of
+    ``make_attn_inputs``, every element an N(0, sigma) draw of a seeded torch generator (all blocks hold finite values;
+    there is no sentinel).  Lengths and block tables are those of ``sess``."""
+    import torch
+    if cfg.dtype != "bf16":
+        raise ValueError("device-drawn inputs are bf16")
+    gen = torch.Generator(device=device)
+    gen.manual_seed((cfg.seed if seed is None else seed) + 13)
+
+    def draw(shape):
+        out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+        step = max(1, (1 << 28) // max(1, int(np.prod(shape[1:]))))        # fp32 staging of at most 1 GiB at a time
+        for a in range(0, shape[0], step):
+            b = min(shape[0], a + step)
+            x = torch.randn((b - a,) + tuple(shape[1:]), generator=gen, device=device, dtype=torch.float32)
+            out[a:b] = (x * cfg.sigma).to(torch.bfloat16)
+        return out
+    pshape = (cfg.n_blocks, cfg.block_size, cfg.n_kv_heads, cfg.head_dim)
+    T = sess.total_new_tokens
+    return (draw(pshape), draw(pshape), draw((T, cfg.n_q_heads, cfg.head_dim)),
+            draw((T, cfg.n_kv_heads, cfg.head_dim)), draw((T, cfg.n_kv_heads, cfg.head_dim)))
