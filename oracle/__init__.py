@@ -51,6 +51,9 @@ def _load():
         for fn in (lib.oracle_kv_pack_layers, lib.oracle_kv_unpack_layers):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp, i32, i32]
+        lib.oracle_kv_copy_batch_layers.restype = C.c_int
+        lib.oracle_kv_copy_batch_layers.argtypes = [i32, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, i32, vp,
+                                                    i32, i32]
         for fn in (lib.oracle_kv_pack_tail, lib.oracle_kv_unpack_tail):
             fn.restype = C.c_int
             fn.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, i32, vp]
@@ -284,6 +287,35 @@ def kv_unpack_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, 
                                          int(layer_begin), int(layer_end))
     if rc != 0:
         raise RuntimeError("oracle_kv_unpack_layers failed")
+
+
+def _batch_layers(to_buffer, k_pool, v_pool, table, prefix_lens, offsets, buf, layer_begin, layer_end):
+    L, nb, bs, hkv, d, eb, ls, bst = _pool_geometry(k_pool, v_pool)
+    table = _check(table, np.int32, "table")
+    prefix_lens = _check(prefix_lens, np.int32, "prefix_lens")
+    offsets = _check(offsets, np.int64, "offsets")
+    buf = _check(buf, k_pool.dtype, "buf")
+    S = prefix_lens.shape[0]
+    if buf.size != int(offsets[S]) * 2 * L * hkv * d:
+        raise ValueError("buffer size does not match the sessions")
+    rc = _load().oracle_kv_copy_batch_layers(1 if to_buffer else 0, _ptr(k_pool), _ptr(v_pool), ls, bst, L, bs, hkv, d, eb,
+                                             _ptr(table), table.shape[1], _ptr(prefix_lens), _ptr(offsets), S, _ptr(buf),
+                                             int(layer_begin), int(layer_end))
+    if rc != 0:
+        raise RuntimeError("oracle_kv_copy_batch_layers failed")
+
+
+def kv_pack_batch_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+                         offsets: np.ndarray, buf: np.ndarray, layer_begin: int, layer_end: int) -> None:
+    """Gather layers ``layer_begin .. layer_end-1`` into ``buf`` laid out layer -> session -> K|V -> token (in place):
+    layer l of the whole batch is the contiguous piece of 2 * total rows that starts at row l * 2 * total."""
+    _batch_layers(True, k_pool, v_pool, table, prefix_lens, offsets, buf, layer_begin, layer_end)
+
+
+def kv_unpack_batch_layers(k_pool: np.ndarray, v_pool: np.ndarray, table: np.ndarray, prefix_lens: np.ndarray,
+                           offsets: np.ndarray, buf: np.ndarray, layer_begin: int, layer_end: int) -> None:
+    """Scatter layers ``layer_begin .. layer_end-1`` of a layer-major buffer into the pools (in place)."""
+    _batch_layers(False, k_pool, v_pool, table, prefix_lens, offsets, buf, layer_begin, layer_end)
 
 
 def kv_append(k_pool: np.ndarray, v_pool: np.ndarray, layer: int, k_new: np.ndarray, v_new: np.ndarray,

@@ -152,6 +152,49 @@ int oracle_kv_unpack_layers(void* k_base, void* v_base, int64_t layer_stride, in
                  elem_bytes, table, table_stride, prefix_lens, offsets, n_sessions, (void*)buf, layer_begin, layer_end);
 }
 
+/* The batch-level layer-major buffer: layer first, then session, then K before V, then token.  Sec. 3.3 reads and
+ * writes K,V layer by layer so that a transfer overlaps the inference of the layers that are already there; with the
+ * layer outermost, layer l of the WHOLE batch is one contiguous piece of 2 * total rows (total = offsets[n_sessions])
+ * that one copy moves.  Row (l, s, kv, t) sits at row l * 2 * total + offsets[s] * 2 + kv * P_s + t of the buffer; the
+ * buffer has the size of the session-major one and holds the same rows in another order. */
+void oracle_kv_locate_batch_layers(int64_t layer_stride, int64_t block_stride, int32_t block_size, int32_t n_kv_heads,
+                                   int32_t head_dim, const int32_t* table, int32_t table_stride,
+                                   const int32_t* prefix_lens, const int64_t* offsets, int32_t n_sessions, int32_t s,
+                                   int32_t l, int32_t kv, int32_t t, int64_t* pool_elem, int64_t* buf_elem) {
+  const int64_t row = (int64_t)n_kv_heads * head_dim;
+  const int64_t total = offsets[n_sessions];
+  const int64_t b = table[(int64_t)s * table_stride + t / block_size];
+  const int64_t o = t % block_size;
+  *pool_elem = (int64_t)l * layer_stride + b * block_stride + o * row;
+  *buf_elem = ((int64_t)l * 2 * total + offsets[s] * 2 + (int64_t)kv * prefix_lens[s] + t) * row;
+}
+
+/* Gather (to_buffer) or scatter of layers layer_begin .. layer_end-1 with the batch-level layer-major buffer. */
+int oracle_kv_copy_batch_layers(int to_buffer, void* k_base, void* v_base, int64_t layer_stride, int64_t block_stride,
+                                int32_t n_layers, int32_t block_size, int32_t n_kv_heads, int32_t head_dim,
+                                int32_t elem_bytes, const int32_t* table, int32_t table_stride,
+                                const int32_t* prefix_lens, const int64_t* offsets, int32_t n_sessions, void* buf,
+                                int32_t layer_begin, int32_t layer_end) {
+  if (elem_bytes != 2 && elem_bytes != 4) return -1;
+  if (layer_begin < 0 || layer_end > n_layers || layer_begin > layer_end) return -1;
+  const size_t row_bytes = (size_t)n_kv_heads * head_dim * elem_bytes;
+  for (int32_t l = layer_begin; l < layer_end; ++l)
+    for (int32_t s = 0; s < n_sessions; ++s)
+      for (int32_t kv = 0; kv < 2; ++kv)
+        for (int32_t t = 0; t < prefix_lens[s]; ++t) {
+          int64_t pe, be;
+          oracle_kv_locate_batch_layers(layer_stride, block_stride, block_size, n_kv_heads, head_dim, table,
+                                        table_stride, prefix_lens, offsets, n_sessions, s, l, kv, t, &pe, &be);
+          char* in_pool = (char*)(kv ? v_base : k_base) + pe * elem_bytes;
+          char* in_buf = (char*)buf + be * elem_bytes;
+          if (to_buffer)
+            memcpy(in_buf, in_pool, row_bytes);
+          else
+            memcpy(in_pool, in_buf, row_bytes);
+        }
+  return 0;
+}
+
 /* Write-back of what a turn added (Sec. 3.3: the slower tiers are kept up to date with newly generated K,V, layer by
  * layer): only tokens tail_begin[s] .. prefix_lens[s]-1 of each session move.  The buffer has the layout of a whole
  * migration buffer for sessions of tail length T_s = prefix_lens[s] - tail_begin[s]: offsets[] counts tail tokens,

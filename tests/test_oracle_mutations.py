@@ -29,6 +29,10 @@ MUTATIONS = {
     "unit_v_rows_not_behind_the_k_rows": ("(chunk_rows[u] + (int64_t)kv * unit_lens[u] + t) * row", "(chunk_rows[u] + t) * row"),
     "unit_chunk_of_the_first_unit": ("(chunk_rows[u] + (int64_t)kv * unit_lens[u] + t) * row", "(chunk_rows[0] + (int64_t)kv * unit_lens[u] + t) * row"),
     "unit_slot_from_the_first_table_row": ("table[(int64_t)u * table_stride + t / block_size];", "table[t / block_size];"),
+    "batch_layer_major_with_v_before_k": ("offsets[s] * 2 + (int64_t)kv * prefix_lens[s] + t) * row",
+                                          "offsets[s] * 2 + (int64_t)(1 - kv) * prefix_lens[s] + t) * row"),
+    "batch_layer_major_layer_stride_of_one_session": ("*buf_elem = ((int64_t)l * 2 * total + offsets[s] * 2",
+                                                      "*buf_elem = ((int64_t)l * 2 * prefix_lens[s] + offsets[s] * 2"),
     "row_map_names_the_other_pool": ("kv_of_row[be / row] = (uint8_t)kv;", "kv_of_row[be / row] = (uint8_t)(1 - kv);"),
     # the residency oracle (priority.py)
     "admits_later_layers_first": ("keyed.append((layer, -blocks_of(n_tokens, block_size), sid))",

@@ -294,6 +294,69 @@ def test_layer_ranges_compose_to_the_whole(oracle_mod):
     assert got_k.tobytes() == ref_k.tobytes() and got_v.tobytes() == ref_v.tobytes()
 
 
+def test_batch_layer_major_buffer_tagged_pool(oracle_mod):
+    """The layer -> session -> K|V -> token buffer: walk it in that order and state, from the layout rule alone, which
+    tagged pool row every position must hold; untouched layers keep their sentinel; a layer of the whole batch is one
+    contiguous piece of 2 * total rows at row l * 2 * total."""
+    cfg = small_cfg("fp32", n_sessions=4, n_layers=3, prefix_dist=("uniform", 0, 23))
+    sess = W.make_sessions(cfg, 8)
+    k_pool, v_pool = tagged_pools(cfg)
+    H, d, bs, L = cfg.n_kv_heads, cfg.head_dim, cfg.block_size, cfg.n_layers
+    row, total = H * d, sess.total_prefix_tokens
+    for lo, hi in ((0, 3), (1, 2), (2, 3), (1, 1)):
+        buf = np.full(total * 2 * L * row, -5.0, dtype=np.float32)
+        oracle_mod.kv_pack_batch_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, buf,
+                                        lo, hi)
+        kv, l, b, o, g, c = decode_tag(buf.view(np.uint32), cfg)
+        pos = 0
+        for layer in range(L):
+            assert pos == layer * 2 * total * row                       # one contiguous piece per layer
+            for s in range(sess.n_sessions):
+                for which in (0, 1):
+                    for tok in range(int(sess.prefix_lens[s])):
+                        sl = slice(pos, pos + row)
+                        if lo <= layer < hi:
+                            assert np.all(kv[sl] == which) and np.all(l[sl] == layer)
+                            assert np.all(b[sl] == sess.block_table[s, tok // bs]) and np.all(o[sl] == tok % bs)
+                            assert np.array_equal(g[sl], np.repeat(np.arange(H), d))
+                            assert np.array_equal(c[sl], np.tile(np.arange(d), H))
+                        else:
+                            assert np.all(buf[sl] == -5.0)
+                        pos += row
+        assert pos == buf.size
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_batch_layer_major_buffer_is_the_session_major_one_reordered(oracle_mod, dtype):
+    """Same rows, other order: cut the session-major buffer (pinned above) into its (session, layer) chunks with numpy
+    and concatenate them layer by layer; scatter from the layer-major buffer into a fresh table and gather again."""
+    cfg = small_cfg(dtype, n_sessions=5, n_layers=3, n_blocks=96, prefix_dist=("uniform", 0, 30), fresh_tables=True)
+    sess = W.make_sessions(cfg, 12)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 5)
+    row, L = cfg.row_elems, cfg.n_layers
+    sm = oracle_mod.kv_pack(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets)
+    pieces = []
+    for layer in range(L):
+        for s in range(sess.n_sessions):
+            P = int(sess.prefix_lens[s])
+            a = (int(sess.buf_token_offsets[s]) * 2 * L + 2 * layer * P) * row
+            pieces.append(sm[a: a + 2 * P * row])
+    expect = np.concatenate(pieces)
+    lm = np.zeros_like(sm)
+    oracle_mod.kv_pack_batch_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, lm, 0, L)
+    assert lm.tobytes() == expect.tobytes()
+    # scatter through the fresh table, layer ranges one at a time, then the session-major gather from there is `sm`
+    k2, v2 = k_pool.copy(), v_pool.copy()
+    for layer in range(L):
+        oracle_mod.kv_unpack_batch_layers(k2, v2, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, lm,
+                                          layer, layer + 1)
+    again = oracle_mod.kv_pack(k2, v2, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets)
+    assert again.tobytes() == sm.tobytes()
+    # and nothing but the destination slots changed
+    changed_k = np.nonzero((k2 != k_pool).reshape(L, cfg.n_blocks, -1).any(axis=2))
+    assert set(changed_k[1]) <= set(sess.owned_blocks(dst=True).tolist())
+
+
 def test_append_places_rows_by_position(oracle_mod):
     """Appended K,V rows land at position P_s + i of their session (checked with tagged new rows and by reading the
     pools back through the table, a numpy route), and every other element of the pools keeps its tag."""
