@@ -119,6 +119,24 @@ int32_t symph_kv_unpack_layers(const symph_kv_cache* cache, int32_t layer_begin,
                                const void* d_buf, int64_t buf_bytes, void* stream);
 
 /*
+ * The same layer-range gather / scatter with a BATCH-LEVEL LAYER-MAJOR buffer (Sec. 3.3, layer-wise reads and writes):
+ * layer first, then session, then K before V, then token, i.e. row (l, s, K|V, t) starts
+ *   (l * 2 * total_tokens + offsets[s] * 2 + kv * P_s + t)
+ * rows into the buffer.  Layer l of the WHOLE batch is then one contiguous piece of 2 * total_tokens rows, which one
+ * copy moves (symph_stage_batch_layers_*), where the session-major buffer above needs one copy per session and layer.
+ * Same size as the session-major buffer, same rows in another order; everything else as for symph_kv_pack_layers.
+ */
+int32_t symph_kv_pack_batch_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                   const int32_t* d_block_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                                   const int64_t* d_buf_token_offsets, int32_t n_sessions, int64_t total_tokens,
+                                   void* d_buf, int64_t buf_bytes, void* stream);
+int32_t symph_kv_unpack_batch_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                     const int32_t* d_dst_block_table, int32_t table_stride,
+                                     const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets,
+                                     int32_t n_sessions, int64_t total_tokens, const void* d_buf, int64_t buf_bytes,
+                                     void* stream);
+
+/*
  * Write-back of what a turn added (Sec. 3.3: the slower memory tiers are kept up to date with newly generated K,V, so
  * that the fast tier can be purged at any time): the gather / scatter for tokens d_tail_begin[s] .. d_prefix_lens[s]-1
  * of every session only, all layers.  The buffer has the layout of a migration buffer for sessions of the tail lengths
@@ -274,6 +292,19 @@ int32_t symph_stage_layer_to_host(void* h_pinned, const void* d_buf, const symph
 int32_t symph_stage_layer_to_device(void* d_buf, const void* h_pinned, const symph_kv_cache* cache, int32_t layer,
                                     const int32_t* h_prefix_lens, const int64_t* h_buf_token_offsets,
                                     int32_t n_sessions, void* consumer_stream, void* side_stream, void* event);
+
+/*
+ * Host staging of layers layer_begin .. layer_end-1 of a batch-level layer-major buffer (see symph_kv_pack_batch_layers):
+ * ONE copy of (layer_end - layer_begin) * 2 * total_tokens rows on `side_stream`, at the same offset in the device
+ * buffer and in the pinned host buffer (which has the size of the whole device buffer); ordering through `event` as for
+ * symph_stage_to_host / symph_stage_to_device.  Needs no host copies of the lengths.
+ */
+int32_t symph_stage_batch_layers_to_host(void* h_pinned, const void* d_buf, const symph_kv_cache* cache,
+                                         int32_t layer_begin, int32_t layer_end, int64_t total_tokens,
+                                         void* producer_stream, void* side_stream, void* event);
+int32_t symph_stage_batch_layers_to_device(void* d_buf, const void* h_pinned, const symph_kv_cache* cache,
+                                           int32_t layer_begin, int32_t layer_end, int64_t total_tokens,
+                                           void* consumer_stream, void* side_stream, void* event);
 
 /*
  * Unit-wise gather / scatter (Sec. 3.3, priority-based K,V cache: single layers of sessions are moved in, lower layers

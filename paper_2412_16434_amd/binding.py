@@ -15,7 +15,8 @@ SYMPH_BF16, SYMPH_FP32 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "symph_kv_buffer_bytes", "symph_kv_pack", "symph_kv_unpack", "symph_kv_pack_layers", "symph_kv_unpack_layers",
-    "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_pack_units", "symph_kv_unpack_units", "symph_kv_append",
+    "symph_kv_pack_batch_layers", "symph_kv_unpack_batch_layers", "symph_stage_batch_layers_to_host",
+    "symph_stage_batch_layers_to_device", "symph_kv_pack_tail", "symph_kv_unpack_tail", "symph_kv_pack_units", "symph_kv_unpack_units", "symph_kv_append",
     "symph_prefix_prefill_attn", "symph_prefix_prefill_attn_workspace_bytes", "symph_prefix_prefill_attn_tuned",
     "symph_prefix_prefill_attn_workspace_bytes_tuned", "symph_prefix_prefill_attn_static", "symph_debug_attn_flags", "symph_stage_to_host",
     "symph_stage_to_device", "symph_stage_layer_to_host", "symph_stage_layer_to_device", "symph_device_copy",
@@ -74,9 +75,13 @@ def load_library():
     for fn in (lib.symph_kv_pack, lib.symph_kv_unpack):
         fn.restype = i32
         fn.argtypes = [cp, vp, i32, vp, vp, i32, i64, vp, i64, vp]
-    for fn in (lib.symph_kv_pack_layers, lib.symph_kv_unpack_layers):
+    for fn in (lib.symph_kv_pack_layers, lib.symph_kv_unpack_layers, lib.symph_kv_pack_batch_layers,
+               lib.symph_kv_unpack_batch_layers):
         fn.restype = i32
         fn.argtypes = [cp, i32, i32, vp, i32, vp, vp, i32, i64, vp, i64, vp]
+    for fn in (lib.symph_stage_batch_layers_to_host, lib.symph_stage_batch_layers_to_device):
+        fn.restype = i32
+        fn.argtypes = [vp, vp, cp, i32, i32, i64, vp, vp, vp]
     for fn in (lib.symph_kv_pack_tail, lib.symph_kv_unpack_tail):
         fn.restype = i32
         fn.argtypes = [cp, vp, i32, vp, vp, vp, i32, i64, vp, i64, vp]
@@ -277,6 +282,36 @@ def kv_unpack_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block
                      buf_token_offsets, total_tokens: int, buf, stream=None) -> None:
     _migrate("symph_kv_unpack_layers", cache, (int(layer_begin), int(layer_end)), dst_block_table, prefix_lens, (),
              buf_token_offsets, total_tokens, buf, stream)
+
+
+def kv_pack_batch_layers(cache: KVCache, layer_begin: int, layer_end: int, block_table, prefix_lens, buf_token_offsets,
+                         total_tokens: int, buf, stream=None) -> None:
+    """Gather layers ``layer_begin .. layer_end-1`` into ``buf`` laid out layer -> session -> K|V -> token."""
+    _migrate("symph_kv_pack_batch_layers", cache, (int(layer_begin), int(layer_end)), block_table, prefix_lens, (),
+             buf_token_offsets, total_tokens, buf, stream)
+
+
+def kv_unpack_batch_layers(cache: KVCache, layer_begin: int, layer_end: int, dst_block_table, prefix_lens,
+                           buf_token_offsets, total_tokens: int, buf, stream=None) -> None:
+    _migrate("symph_kv_unpack_batch_layers", cache, (int(layer_begin), int(layer_end)), dst_block_table, prefix_lens, (),
+             buf_token_offsets, total_tokens, buf, stream)
+
+
+def stage_batch_layers_to_host(h_pinned, d_buf, cache: KVCache, layer_begin: int, layer_end: int, total_tokens: int,
+                               producer_stream, side_stream, event) -> None:
+    """One copy of the layers' contiguous piece of a layer-major buffer, device -> pinned host, on ``side_stream``."""
+    st = cache.struct()
+    _check(load_library().symph_stage_batch_layers_to_host(
+        _ptr(h_pinned), _ptr(d_buf), C.byref(st), int(layer_begin), int(layer_end), int(total_tokens),
+        _stream_ptr(producer_stream), _stream_ptr(side_stream), _event_ptr(event)), "symph_stage_batch_layers_to_host")
+
+
+def stage_batch_layers_to_device(d_buf, h_pinned, cache: KVCache, layer_begin: int, layer_end: int, total_tokens: int,
+                                 consumer_stream, side_stream, event) -> None:
+    st = cache.struct()
+    _check(load_library().symph_stage_batch_layers_to_device(
+        _ptr(d_buf), _ptr(h_pinned), C.byref(st), int(layer_begin), int(layer_end), int(total_tokens),
+        _stream_ptr(consumer_stream), _stream_ptr(side_stream), _event_ptr(event)), "symph_stage_batch_layers_to_device")
 
 
 def _units(fn_name, slots: KVCache, unit_table, unit_lens, unit_token_offsets, unit_chunk_rows, total_unit_tokens, buf,

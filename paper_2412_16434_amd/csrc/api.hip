@@ -22,7 +22,7 @@ static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_beg
                        const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
                        const int64_t* d_offsets, int32_t n_sessions, int64_t total_tokens, void* d_buf,
                        int64_t buf_bytes, void* stream, const int32_t* d_tail_begin = nullptr,
-                       const int64_t* d_chunk_rows = nullptr) {
+                       const int64_t* d_chunk_rows = nullptr, bool batch_layer_major = false) {
   int32_t rc = validate_cache(cache);
   if (rc != SYMPH_OK) return rc;
   if (n_sessions < 0 || total_tokens < 0 || table_stride < 0 || buf_bytes < 0) return SYMPH_EINVAL;
@@ -33,7 +33,8 @@ static int32_t migrate(bool pack, const symph_kv_cache* cache, int32_t layer_beg
   if (need < 0) return SYMPH_EINVAL;
   if (buf_bytes < need) return SYMPH_EWORKSPACE;
   return launch_kv_migrate(pack, cache, layer_begin, layer_end, d_table, table_stride, d_prefix_lens, d_tail_begin,
-                           d_offsets, n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream, d_chunk_rows);
+                           d_offsets, n_sessions, total_tokens, d_buf, buf_bytes, (hipStream_t)stream, d_chunk_rows,
+                           batch_layer_major);
 }
 
 // Units (single layers of sessions) between one pool of slots and chunks placed anywhere in the buffer.
@@ -112,6 +113,63 @@ int32_t symph_kv_pack_layers(const symph_kv_cache* cache, int32_t layer_begin, i
                              int64_t buf_bytes, void* stream) {
   return migrate(true, cache, layer_begin, layer_end, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets,
                  n_sessions, total_tokens, d_buf, buf_bytes, stream);
+}
+
+int32_t symph_kv_pack_batch_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                   const int32_t* d_block_table, int32_t table_stride, const int32_t* d_prefix_lens,
+                                   const int64_t* d_buf_token_offsets, int32_t n_sessions, int64_t total_tokens,
+                                   void* d_buf, int64_t buf_bytes, void* stream) {
+  return migrate(true, cache, layer_begin, layer_end, d_block_table, table_stride, d_prefix_lens, d_buf_token_offsets,
+                 n_sessions, total_tokens, d_buf, buf_bytes, stream, nullptr, nullptr, true);
+}
+
+int32_t symph_kv_unpack_batch_layers(const symph_kv_cache* cache, int32_t layer_begin, int32_t layer_end,
+                                     const int32_t* d_dst_block_table, int32_t table_stride,
+                                     const int32_t* d_prefix_lens, const int64_t* d_buf_token_offsets,
+                                     int32_t n_sessions, int64_t total_tokens, const void* d_buf, int64_t buf_bytes,
+                                     void* stream) {
+  return migrate(false, cache, layer_begin, layer_end, d_dst_block_table, table_stride, d_prefix_lens,
+                 d_buf_token_offsets, n_sessions, total_tokens, const_cast<void*>(d_buf), buf_bytes, stream, nullptr,
+                 nullptr, true);
+}
+
+// One contiguous copy of layers layer_begin .. layer_end-1 of a batch-level layer-major buffer.
+static int32_t stage_batch_layers(bool to_host, void* dst, const void* src, const symph_kv_cache* cache,
+                                  int32_t layer_begin, int32_t layer_end, int64_t total_tokens, void* other_stream,
+                                  void* side_stream, void* event) {
+  int32_t rc = validate_cache(cache);
+  if (rc != SYMPH_OK) return rc;
+  if (layer_begin < 0 || layer_end > cache->n_layers || layer_begin > layer_end || total_tokens < 0) return SYMPH_EINVAL;
+  if (layer_begin == layer_end || total_tokens == 0) return SYMPH_OK;
+  if (!dst || !src || !event || side_stream == other_stream) return SYMPH_EINVAL;
+  const int64_t layer_bytes = 2 * total_tokens * (int64_t)cache->n_kv_heads * cache->head_dim * elem_bytes_of(cache->dtype);
+  const int64_t begin = layer_begin * layer_bytes, bytes = (layer_end - layer_begin) * layer_bytes;
+  if (to_host) {  // the copy follows what the producer has enqueued so far
+    if (hipEventRecord((hipEvent_t)event, (hipStream_t)other_stream) != hipSuccess) return SYMPH_ELAUNCH;
+    if (hipStreamWaitEvent((hipStream_t)side_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
+  }
+  if (hipMemcpyAsync((char*)dst + begin, (const char*)src + begin, (size_t)bytes,
+                     to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, (hipStream_t)side_stream) != hipSuccess)
+    return SYMPH_ELAUNCH;
+  if (!to_host) {  // the consumer waits for the copy
+    if (hipEventRecord((hipEvent_t)event, (hipStream_t)side_stream) != hipSuccess) return SYMPH_ELAUNCH;
+    if (hipStreamWaitEvent((hipStream_t)other_stream, (hipEvent_t)event, 0) != hipSuccess) return SYMPH_ELAUNCH;
+  }
+  return SYMPH_OK;
+}
+
+int32_t symph_stage_batch_layers_to_host(void* h_pinned, const void* d_buf, const symph_kv_cache* cache,
+                                         int32_t layer_begin, int32_t layer_end, int64_t total_tokens,
+                                         void* producer_stream, void* side_stream, void* event) {
+  return stage_batch_layers(true, h_pinned, d_buf, cache, layer_begin, layer_end, total_tokens, producer_stream,
+                            side_stream, event);
+}
+
+int32_t symph_stage_batch_layers_to_device(void* d_buf, const void* h_pinned, const symph_kv_cache* cache,
+                                           int32_t layer_begin, int32_t layer_end, int64_t total_tokens,
+                                           void* consumer_stream, void* side_stream, void* event) {
+  return stage_batch_layers(false, d_buf, h_pinned, cache, layer_begin, layer_end, total_tokens, consumer_stream,
+                            side_stream, event);
 }
 
 int32_t symph_kv_pack_tail(const symph_kv_cache* cache, const int32_t* d_block_table, int32_t table_stride,

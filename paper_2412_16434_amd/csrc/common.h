@@ -29,7 +29,7 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* cache, int32_t layer_
                           const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
                           const int32_t* d_tail_begin, const int64_t* d_offsets, int32_t n_sessions,
                           int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream,
-                          const int64_t* d_chunk_rows = nullptr);
+                          const int64_t* d_chunk_rows = nullptr, bool batch_layer_major = false);
 int32_t launch_kv_append(const symph_kv_cache* cache, int32_t layer, const void* d_k_new, const void* d_v_new,
                          const int32_t* d_cu_new_lens, const int32_t* d_prefix_lens, const int32_t* d_table,
                          int32_t table_stride, int32_t n_sessions, int32_t total_new_tokens, hipStream_t stream);

@@ -40,6 +40,8 @@ struct MigrateParams {
   char* buf;
   int64_t buf_bytes;
   int32_t xcd_chunk;  // > 0: workgroups per XCD in the XCD-contiguous mapping of blockIdx.x; 0: identity mapping
+  int64_t batch_layer_b;  // 0: session-major buffer (a session's layers follow each other); else the bytes of one layer
+                          // of the WHOLE batch in the layer-major buffer (layer, then session, then K|V, then token)
 };
 
 template <typename VecT, int NT>
@@ -101,14 +103,21 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   const int32_t b = p.table[(int64_t)s * p.table_stride + j];
   if (b < 0 || b >= p.n_blocks) return;  // not a block of this cache: touch nothing
   const int32_t slot = t - j * p.block_size;
-  const int64_t plane_b = (int64_t)P * p.row_bytes;  // one (layer, K|V) plane of this session in the buffer
+  // Plane pl = (layer, K|V) of this session starts at sess_b + (pl / 2) * layer_b + (pl % 2) * plane_b of the buffer.
+  const int64_t plane_b = (int64_t)P * p.row_bytes;
   int64_t sess_b = off_s * p.n_planes * p.row_bytes;
+  int64_t layer_b = 2 * plane_b;
+  if (p.batch_layer_b) {
+    sess_b = off_s * 2 * p.row_bytes;
+    layer_b = p.batch_layer_b;
+  }
   if (p.chunk_rows) {
     const int64_t first_row = p.chunk_rows[s];
     if (first_row < 0 || first_row > p.buf_bytes / p.row_bytes) return;  // (the second test also keeps the product in range)
     sess_b = first_row * p.row_bytes;
   }
-  if (sess_b + plane_b * p.n_planes > p.buf_bytes) return;  // the session would not fit the buffer: touch nothing
+  // the session's last plane would not fit the buffer: touch nothing
+  if (sess_b + (int64_t)(p.n_planes / 2 - 1) * layer_b + 2 * plane_b > p.buf_bytes) return;
 
   const int64_t pool_off = (int64_t)b * p.block_stride_b + (int64_t)slot * p.row_bytes + (int64_t)col * sizeof(VecT);
   const int64_t buf_off0 = sess_b + t64 * p.row_bytes + (int64_t)col * sizeof(VecT);
@@ -119,14 +128,14 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   for (int i = 0; i < PLANES; ++i) {
     const int32_t pl = min(plane0 + i, p.plane_end - 1);  // a ragged last group repeats its last plane (same bytes)
     const char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
-    v[i] = PACK ? load_vec<VecT, NT>(pool) : load_vec<VecT, NT>(p.buf + buf_off0 + pl * plane_b);
+    v[i] = PACK ? load_vec<VecT, NT>(pool) : load_vec<VecT, NT>(p.buf + buf_off0 + (pl >> 1) * layer_b + (pl & 1) * plane_b);
   }
 #pragma unroll
   for (int i = 0; i < PLANES; ++i) {
     const int32_t pl = min(plane0 + i, p.plane_end - 1);
     char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off;
     if (PACK)
-      store_vec<VecT, NT>(p.buf + buf_off0 + pl * plane_b, v[i]);
+      store_vec<VecT, NT>(p.buf + buf_off0 + (pl >> 1) * layer_b + (pl & 1) * plane_b, v[i]);
     else
       store_vec<VecT, NT>(pool, v[i]);
   }
@@ -166,7 +175,7 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begi
                           const int32_t* d_table, int32_t table_stride, const int32_t* d_prefix_lens,
                           const int32_t* d_tail_begin, const int64_t* d_offsets, int32_t n_sessions,
                           int64_t total_tokens, void* d_buf, int64_t buf_bytes, hipStream_t stream,
-                          const int64_t* d_chunk_rows) {
+                          const int64_t* d_chunk_rows, bool batch_layer_major) {
   const int eb = elem_bytes_of(c->dtype);
   const int64_t row_bytes = (int64_t)c->n_kv_heads * c->head_dim * eb;
   if (row_bytes > 0x7FFFFFFF) return SYMPH_EUNSUPPORTED;
@@ -202,6 +211,7 @@ int32_t launch_kv_migrate(bool pack, const symph_kv_cache* c, int32_t layer_begi
   p.total_tokens = total_tokens;
   p.buf = (char*)d_buf;
   p.buf_bytes = buf_bytes;
+  p.batch_layer_b = batch_layer_major ? 2 * total_tokens * row_bytes : 0;
 
   // Planes per lane, measured on MI355X (config 2 / config 4, TB/s read+written): gather 1 -> 6.1 / 5.6,
   // 2 -> 5.8 / 5.9, 4 -> 5.5 / 5.7, 8 -> 3.0; scatter 1 -> 5.9 / 5.5, 2 -> 6.5 / 6.2, 4 -> 6.3 / 6.2.  One plane per

@@ -124,3 +124,94 @@ def test_layer_wise_staging_to_host(oracle_mod):
         S.stage_layer_to_host(host, dbuf, cache, l, h_prefix, h_off, s_pack, s_copy, evs[l])
     torch.cuda.synchronize()
     assert host.numpy().view(np.uint16).tobytes() == whole.tobytes()
+
+
+@pytest.mark.parametrize("lo,hi", [(0, 1), (5, 6), (2, 5), (0, 6), (3, 3)])
+@pytest.mark.parametrize("shape", ["llama rows", "fp32 240-byte rows"])
+def test_batch_layer_major_pack_and_unpack(oracle_mod, lo, hi, shape):
+    """symph_kv_pack_batch_layers / symph_kv_unpack_batch_layers (buffer laid out layer -> session -> K|V -> token)
+    against the oracle's, bit for bit, including the buffer and pool bytes that must not change."""
+    cfg = _cfg(n_kv_heads=8) if shape == "llama rows" else _cfg(dtype="fp32", n_kv_heads=3, head_dim=20, block_size=4,
+                                                                n_blocks=512, n_q_heads=3)
+    sess = W.make_sessions(cfg, 5)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 5)
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    total = sess.total_prefix_tokens
+    n_elems = sess.payload_bytes() // k_pool.itemsize
+    fill = W.SENTINEL16 if k_pool.dtype == np.uint16 else np.float32(-7.5)
+
+    ref_buf = np.full(n_elems, fill, dtype=k_pool.dtype)
+    oracle_mod.kv_pack_batch_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, ref_buf,
+                                    lo, hi)
+    buf = to_dev(np.full(n_elems, fill, dtype=k_pool.dtype))
+    S.kv_pack_batch_layers(cache, lo, hi, ds.table, ds.prefix_lens, ds.offsets, total, buf)
+    torch.cuda.synchronize()
+    assert to_host(buf).tobytes() == ref_buf.tobytes(), "layer-major pack of a layer range differs from the oracle"
+
+    whole = np.zeros(n_elems, dtype=k_pool.dtype)
+    oracle_mod.kv_pack_batch_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, whole, 0,
+                                    cfg.n_layers)
+    ref_k, ref_v = np.full_like(k_pool, fill), np.full_like(v_pool, fill)
+    oracle_mod.kv_unpack_batch_layers(ref_k, ref_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets, whole,
+                                      lo, hi)
+    dcache = S.KVCache(to_dev(np.full_like(k_pool, fill)), to_dev(np.full_like(v_pool, fill)))
+    S.kv_unpack_batch_layers(dcache, lo, hi, ds.dst_table, ds.prefix_lens, ds.offsets, total, to_dev(whole))
+    torch.cuda.synchronize()
+    assert to_host(dcache.k_pool).tobytes() == ref_k.tobytes(), "layer-major unpack of a layer range: K pool differs"
+    assert to_host(dcache.v_pool).tobytes() == ref_v.tobytes(), "layer-major unpack of a layer range: V pool differs"
+
+
+def test_layer_major_resume_one_copy_per_layer(oracle_mod):
+    """A resume whose buffer sits in pinned host memory in the layer-major layout: ONE host->device copy per layer
+    (side stream), the unpack of that layer (second stream), attention on it (third stream), each released by the event
+    of the step before.  Final pools must be those of the oracle's scatter, every layer's attention output the oracle's;
+    then the way back: layer-major pack of every layer and one copy per layer to the host gives the oracle's buffer."""
+    cfg = _cfg(n_layers=5, n_sessions=5, n_blocks=160)
+    sess = W.make_sessions(cfg, 9)
+    k_pool, v_pool = W.make_pool_host(cfg, sess, 9)
+    L, total = cfg.n_layers, sess.total_prefix_tokens
+    n_elems = sess.payload_bytes() // 2
+    ref_buf = np.zeros(n_elems, dtype=np.uint16)
+    oracle_mod.kv_pack_batch_layers(k_pool, v_pool, sess.block_table, sess.prefix_lens, sess.buf_token_offsets, ref_buf, 0, L)
+    ref_k, ref_v = k_pool.copy(), v_pool.copy()
+    oracle_mod.kv_unpack_batch_layers(ref_k, ref_v, sess.dst_block_table, sess.prefix_lens, sess.buf_token_offsets,
+                                      ref_buf, 0, L)
+    _, _, q, k_new, v_new = W.make_attn_inputs(cfg, sess, 9)
+    ds = DeviceSessions(sess)
+    cache = S.KVCache(to_dev(k_pool), to_dev(v_pool))
+    host = torch.from_numpy(ref_buf.view(np.int16).copy()).pin_memory()
+    dbuf = torch.zeros(n_elems, dtype=torch.int16, device=DEV)
+    qd, knd, vnd = to_dev(q), to_dev(k_new), to_dev(v_new)
+    outs = [torch.full_like(qd, float("nan")) for _ in range(L)]
+    ws_bytes = S.prefix_prefill_attn_workspace_bytes(cache, sess.n_sessions, cfg.n_q_heads, sess.total_new_tokens,
+                                                     sess.max_new_len, sess.max_prefix_len)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    s_copy, s_unpack, s_attn = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    ev_copy = [torch.cuda.Event() for _ in range(L)]
+    ev_unpack = [torch.cuda.Event() for _ in range(L)]
+    torch.cuda.synchronize()
+    for l in range(L):
+        S.stage_batch_layers_to_device(dbuf, host, cache, l, l + 1, total, s_unpack, s_copy, ev_copy[l])
+        S.kv_unpack_batch_layers(cache, l, l + 1, ds.dst_table, ds.prefix_lens, ds.offsets, total, dbuf, stream=s_unpack)
+        ev_unpack[l].record(s_unpack)
+        s_attn.wait_event(ev_unpack[l])
+        S.prefix_prefill_attn(cache, l, qd, knd, vnd, outs[l], ds.cu_new_lens, ds.prefix_lens, ds.dst_table,
+                              sess.max_new_len, sess.max_prefix_len, cfg.scale, workspace=ws, stream=s_attn)
+    torch.cuda.synchronize()
+    assert to_host(cache.k_pool).tobytes() == ref_k.tobytes() and to_host(cache.v_pool).tobytes() == ref_v.tobytes()
+    for l in range(L):
+        ref = oracle_mod.prefix_prefill_attn(ref_k, ref_v, q, k_new, v_new, sess.cu_new_lens, sess.prefix_lens,
+                                             sess.dst_block_table, cfg.scale, layer=l)
+        max_abs, rel = attn_errors(to_host(outs[l]), ref)
+        assert max_abs <= TOL["bf16"][0] and rel <= TOL["bf16"][1], f"layer {l}: {max_abs} {rel}"
+    # write-back: gather from the destination blocks layer by layer, one copy per layer
+    host2 = torch.zeros(n_elems, dtype=torch.int16).pin_memory()
+    dbuf.zero_()
+    ev_pack = [torch.cuda.Event() for _ in range(L)]
+    torch.cuda.synchronize()
+    for l in range(L):
+        S.kv_pack_batch_layers(cache, l, l + 1, ds.dst_table, ds.prefix_lens, ds.offsets, total, dbuf, stream=s_unpack)
+        S.stage_batch_layers_to_host(host2, dbuf, cache, l, l + 1, total, s_unpack, s_copy, ev_pack[l])
+    torch.cuda.synchronize()
+    assert host2.numpy().view(np.uint16).tobytes() == ref_buf.tobytes()
