@@ -584,13 +584,15 @@ def write_traffic_summary(args):
     payload = sess.payload_bytes()
 
     def means(d, counter):
+        """kernel name -> (mean reading, launches) over the launches with that kernel's LARGEST grid: the run also
+        launches the same instantiations on smaller inputs (the write-back of a turn, the unit-wise scatter)."""
         acc = {}
         for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
             with open(f) as fh:
                 for r in csv.DictReader(fh):
                     if r.get("Counter_Name") == counter:
-                        acc.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
-        return {k: (sum(v) / len(v), len(v)) for k, v in acc.items()}
+                        acc.setdefault(r["Kernel_Name"], {}).setdefault(int(r["Grid_Size"]), []).append(float(r["Counter_Value"]))
+        return {k: (sum(g[max(g)]) / len(g[max(g)]), len(g[max(g)])) for k, g in acc.items()}
     fetch, write = means(args.write_traffic_summary[0], "FETCH_SIZE"), means(args.write_traffic_summary[1], "WRITE_SIZE")
 
     def pick(table, *subs):

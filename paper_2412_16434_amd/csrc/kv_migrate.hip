@@ -141,6 +141,95 @@ __global__ __launch_bounds__(256) void kv_migrate_kernel(const MigrateParams p) 
   }
 }
 
+// The same copy with ROWS consecutive tokens per wave (rows that fill whole waves only).  A wave's life is a chain of
+// dependent scalar loads (session search, lengths, block id) followed by one vector load and one store; with every
+// wave slot of the chip taken, the bytes in flight are the waves in their load phase, so a wave that pays for the
+// chain once and then has ROWS loads in flight keeps more of the memory system busy.  The session of the first token
+// is searched for; the following tokens step to the next session when they pass its end.
+template <typename VecT, bool PACK, int ROWS, int PLANES, int NT>
+__global__ __launch_bounds__(256) void kv_migrate_rows_kernel(const MigrateParams p) {
+  int64_t wg = blockIdx.x;
+  if (p.xcd_chunk > 0 && wg < 8 * (int64_t)p.xcd_chunk) wg = (wg & 7) * (int64_t)p.xcd_chunk + (wg >> 3);
+  const int lane = threadIdx.x & 63;
+  const int64_t wave64 = wg * 4 + (threadIdx.x >> 6);
+  const int64_t wave_id = ((int64_t)__builtin_amdgcn_readfirstlane((int32_t)(wave64 >> 32)) << 32) |
+                          (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)wave64);
+  const int wave_shift = p.row_shift - 6;                       // log2(waves per row)
+  const int64_t tg0 = (wave_id >> wave_shift) * ROWS;           // first token of this wave, in the concatenated space
+  const int32_t col = ((int32_t)(wave_id & ((1 << wave_shift) - 1)) << 6) + lane;
+  if (tg0 >= p.total_tokens) return;
+
+  int32_t lo = 0, hi = p.n_sessions;   // session s with offsets[s] <= tg0 < offsets[s+1] (the last match skips empty ones)
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (p.offsets[mid] <= tg0)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  int32_t s = lo;
+  int64_t off_s = p.offsets[s], off_next = p.offsets[s + 1];
+  int64_t pool_off[ROWS], buf_off[ROWS], layer_b[ROWS], plane_b[ROWS];
+  bool ok[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    const int64_t tg = tg0 + r;
+    ok[r] = tg < p.total_tokens;
+    if (ok[r])
+      while (tg >= off_next && s + 1 < p.n_sessions) {   // past the end of the session: the next one with tokens
+        ++s;
+        off_s = off_next;
+        off_next = p.offsets[s + 1];
+      }
+    const int32_t first = p.tail_begin ? p.tail_begin[s] : 0;
+    const int32_t P = p.prefix_lens[s] - first;
+    const int64_t t64 = tg - off_s;
+    ok[r] = ok[r] && first >= 0 && t64 >= 0 && t64 < P;   // inconsistent offsets / lengths: touch nothing
+    const int32_t t = first + (int32_t)t64;
+    const int32_t j = p.bs_shift >= 0 ? (t >> p.bs_shift) : t / p.block_size;
+    ok[r] = ok[r] && j >= 0 && j < p.table_stride;
+    const int32_t b = ok[r] ? p.table[(int64_t)s * p.table_stride + j] : -1;
+    ok[r] = ok[r] && b >= 0 && b < p.n_blocks;            // not a block of this cache: touch nothing
+    const int32_t slot = t - j * p.block_size;
+    plane_b[r] = (int64_t)P * p.row_bytes;
+    layer_b[r] = 2 * plane_b[r];
+    int64_t sess_b = off_s * p.n_planes * p.row_bytes;
+    if (p.batch_layer_b) {
+      sess_b = off_s * 2 * p.row_bytes;
+      layer_b[r] = p.batch_layer_b;
+    }
+    if (p.chunk_rows) {
+      const int64_t first_row = ok[r] ? p.chunk_rows[s] : 0;
+      ok[r] = ok[r] && first_row >= 0 && first_row <= p.buf_bytes / p.row_bytes;
+      sess_b = first_row * p.row_bytes;
+    }
+    ok[r] = ok[r] && sess_b + (int64_t)(p.n_planes / 2 - 1) * layer_b[r] + 2 * plane_b[r] <= p.buf_bytes;
+    pool_off[r] = (int64_t)b * p.block_stride_b + (int64_t)slot * p.row_bytes + (int64_t)col * sizeof(VecT);
+    buf_off[r] = sess_b + t64 * p.row_bytes + (int64_t)col * sizeof(VecT);
+  }
+
+  const int32_t plane0 = p.plane_begin + blockIdx.y * PLANES;
+  VecT v[ROWS][PLANES];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+    for (int i = 0; i < PLANES; ++i) {
+      const int32_t pl = min(plane0 + i, p.plane_end - 1);  // a ragged last group repeats its last plane (same bytes)
+      const char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off[r];
+      const char* in_buf = p.buf + buf_off[r] + (pl >> 1) * layer_b[r] + (pl & 1) * plane_b[r];
+      if (ok[r]) v[r][i] = load_vec<VecT, NT>(PACK ? pool : in_buf);
+    }
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+    for (int i = 0; i < PLANES; ++i) {
+      const int32_t pl = min(plane0 + i, p.plane_end - 1);
+      char* pool = ((pl & 1) ? p.v_base : p.k_base) + (int64_t)(pl >> 1) * p.layer_stride_b + pool_off[r];
+      char* in_buf = p.buf + buf_off[r] + (pl >> 1) * layer_b[r] + (pl & 1) * plane_b[r];
+      if (ok[r]) store_vec<VecT, NT>(PACK ? in_buf : pool, v[r][i]);
+    }
+}
+
 // Non-temporal loads and stores (every byte is touched once): bit 0 loads, bit 1 stores.
 constexpr int kMigrateNT = 3;
 
@@ -152,8 +241,26 @@ static void launch_uniform(dim3 grid, const MigrateParams& p, hipStream_t stream
     hipLaunchKernelGGL((kv_migrate_kernel<VecT, PACK, PLANES, kMigrateNT, false>), grid, dim3(256), 0, stream, p);
 }
 
+template <typename VecT, bool PACK, int ROWS, int PLANES>
+static int32_t launch_rows(const MigrateParams& p_in, hipStream_t stream) {
+  const int64_t n_vec = ceil_div64(p_in.total_tokens, ROWS) * p_in.vecs_per_row;
+  const int64_t gx = ceil_div64(n_vec, 256);
+  const int64_t gy = ceil_div64(p_in.plane_end - p_in.plane_begin, PLANES);
+  if (gx > 0x7FFFFFFFLL || gy > 65535) return SYMPH_EUNSUPPORTED;
+  MigrateParams p = p_in;
+  p.xcd_chunk = PACK ? (int32_t)(gx / 8) : 0;
+  hipLaunchKernelGGL((kv_migrate_rows_kernel<VecT, PACK, ROWS, PLANES, kMigrateNT>), dim3((unsigned)gx, (unsigned)gy),
+                     dim3(256), 0, stream, p);
+  return hipGetLastError() == hipSuccess ? SYMPH_OK : SYMPH_ELAUNCH;
+}
+
 template <typename VecT, bool PACK>
 static int32_t launch_planes(int planes, const MigrateParams& p_in, hipStream_t stream) {
+  // Measured on MI355X, gather with one plane per lane: two consecutive tokens per wave, i.e. one session search for
+  // two loads, +5 % on config 2 (16 sessions: 5.8 -> 6.1 TB/s), four the same, eight a cliff (3.1 TB/s); nothing to
+  // gain with a single session (no search: 6.08 -> 5.99) or in the two-plane form (config 4: 6.5 either way), and the
+  // scatter does not change (6.5 / 5.3 / 5.2 TB/s on configs 2 / 4 / 3 with one, two or four tokens per wave).
+  if (PACK && planes == 1 && p_in.row_shift >= 6 && p_in.n_sessions > 1) return launch_rows<VecT, PACK, 2, 1>(p_in, stream);
   const int64_t n_vec = p_in.total_tokens * p_in.vecs_per_row;
   const int64_t gx = ceil_div64(n_vec, 256);
   const int64_t gy = ceil_div64(p_in.plane_end - p_in.plane_begin, planes);

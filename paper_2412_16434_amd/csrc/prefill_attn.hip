@@ -305,9 +305,23 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     r.nt = r.N <= p.bmt_dec ? 0 : unit_tiles(r.P, r.N, r.t0, p.bmt);
     return r;
   };
+  // A thread's units (u = tid, tid + 256, ...) and the way they are cut are worked out once and kept in registers
+  // between the passes while there are at most kSchedCached of them per thread; longer lists recompute them.
+  constexpr int kSchedCached = 4;
+  const int n_rounds = (U + kSchedThreads - 1) / kSchedThreads;
+  const bool cached = n_rounds <= kSchedCached;
+  Unit uc[kSchedCached];
   // pass 1: total number of (unit, key tile) pairs
   unsigned long long mine = 0;
-  for (int u = tid; u < U; u += kSchedThreads) mine += (unsigned long long)unit(u).nt;
+  if (cached) {
+#pragma unroll
+    for (int r = 0; r < kSchedCached; ++r) {
+      uc[r] = unit(r * kSchedThreads + tid);
+      mine += (unsigned long long)uc[r].nt;
+    }
+  } else {
+    for (int u = tid; u < U; u += kSchedThreads) mine += (unsigned long long)unit(u).nt;
+  }
   if (mine) atomicAdd(&total_tiles_s, mine);
   __syncthreads();
   if (tid == 0) {
@@ -315,31 +329,34 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     // anything but the longest units; with fewer, every unit is cut so that there are about two pieces per slot.
     const long long wg_units = (long long)(U - n_dec) * p.n_kv_heads;
     const int target = (p.coarse_ok && wg_units >= 2ll * p.target_slots) ? p.target_slots : p.target;
+    // C = ceil(total tiles * kv-heads / target): a single-precision estimate, then exact steps in integers
     const unsigned long long tot = total_tiles_s * (unsigned long long)p.n_kv_heads;
-    long long c = (long long)((tot + target - 1) / (unsigned long long)target);
-    if (c < p.c_min) c = p.c_min;
+    long long c = (long long)((float)tot * (1.0f / (float)target));
     if (c > 0x3FFFFFFF) c = 0x3FFFFFFF;
+    while (c < 0x3FFFFFFF && (unsigned long long)c * (unsigned long long)target < tot) ++c;
+    while (c > 0 && (unsigned long long)(c - 1) * (unsigned long long)target >= tot) --c;
+    if (c < p.c_min) c = p.c_min;
     chunk_s = (int)c;
   }
   __syncthreads();
   const int C = chunk_s;
-  // bucket of a chunk length: longer chunks get smaller bucket numbers (they are dispatched first)
+  // bucket of a chunk length: longer chunks get smaller bucket numbers (they are dispatched first).  Any monotone
+  // function of the length will do, as long as both passes below use the same one.
+  const float buckets_per_tile = (float)kSchedBuckets / (float)C;
   auto bucket_of = [&](int len) {
-    long long b = (long long)(C - len) * kSchedBuckets / C;
-    return (int)(b < 0 ? 0 : (b >= kSchedBuckets ? kSchedBuckets - 1 : b));
+    const int b = (int)((float)(C - len) * buckets_per_tile);
+    return b < 0 ? 0 : (b >= kSchedBuckets ? kSchedBuckets - 1 : b);
   };
-  // How this thread's unit of the round starting at `base` is cut: chunks of `len` tiles, n_real of them, in slots
-  // pslot0 .. and with counter `merge` when it is split (n_real > 1).  The running totals of chunks and of split units
-  // (carry_c, carry_m) go through the rounds in unit order; a unit whose chunks would pass the end of the slots or of
-  // the counters stays whole, and so does every split candidate after it.
+  // How a unit is cut: chunks of `len` tiles, n_real of them, in slots pslot0 .. and with counter `merge` when it is
+  // split (n_real > 1).  The running totals of chunks and of split units (carry_c, carry_m) go through the rounds in
+  // unit order; a unit whose chunks would pass the end of the slots or of the counters stays whole, and so does every
+  // split candidate after it.  (Every thread of the block calls this the same number of times: it holds barriers.)
   struct Cut {
-    Unit u;
     int len, n_real, pslot0, merge;
   };
-  auto cut_round = [&](int base, int& carry_c, int& carry_m) {
+  auto cut_of = [&](const Unit& un, int& carry_c, int& carry_m) {
     Cut c;
-    c.u = unit(base + tid);
-    const int nt = c.u.nt;
+    const int nt = un.nt;
     const int nc = nt > 0 ? (nt + C - 1) / C : 0;
     c.len = nc > 0 ? (nt + nc - 1) / nc : 0;
     c.n_real = c.len > 0 ? (nt + c.len - 1) / c.len : 0;
@@ -363,14 +380,27 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     return c;
   };
   // pass 2: histogram of chunk lengths
+  auto count = [&](const Unit& un, const Cut& c) {
+    if (c.n_real == 0) return;
+    const int n_full = un.nt / c.len, rem = un.nt - n_full * c.len;  // n_full chunks of len tiles, one of rem
+    if (n_full) atomicAdd(&hist[bucket_of(c.len)], n_full);
+    if (rem) atomicAdd(&hist[bucket_of(rem)], 1);
+  };
+  Cut cc[kSchedCached];
   {
     int carry_c = 0, carry_m = 0;
-    for (int base = 0; base < U; base += kSchedThreads) {
-      const Cut c = cut_round(base, carry_c, carry_m);
-      if (c.n_real == 0) continue;
-      const int n_full = c.u.nt / c.len, rem = c.u.nt - n_full * c.len;  // n_full chunks of len tiles, one of rem
-      if (n_full) atomicAdd(&hist[bucket_of(c.len)], n_full);
-      if (rem) atomicAdd(&hist[bucket_of(rem)], 1);
+    if (cached) {
+#pragma unroll
+      for (int r = 0; r < kSchedCached; ++r)
+        if (r < n_rounds) {
+          cc[r] = cut_of(uc[r], carry_c, carry_m);
+          count(uc[r], cc[r]);
+        }
+    } else {
+      for (int base = 0; base < U; base += kSchedThreads) {
+        const Unit un = unit(base + tid);
+        count(un, cut_of(un, carry_c, carry_m));
+      }
     }
   }
   __syncthreads();
@@ -387,33 +417,41 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   }
   __syncthreads();
   // pass 3: emit items
-  {
+  auto emit = [&](const Unit& un, const Cut& c) {
+    if (c.n_real == 0) return;
+    if (c.n_real > 1) {
+      atomicMax(&n_pslot_s, c.pslot0 + c.n_real);
+      atomicMax(&n_split_s, c.merge + 1);
+    }
+    const int cu_s = cu_of[un.s];
+    const int32_t* table_row = p.table + (int64_t)un.s * p.table_stride;
+    for (int ch = 0; ch < c.n_real; ++ch) {
+      const int tb = ch * c.len, te = min(un.nt, tb + c.len);
+      const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
+      if (pos < p.items_bound) {
+        WorkItem w{un.s, un.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, un.N, un.P,
+                   c.merge, c.pslot0, c.n_real, {-1, -1, -1, -1, -1, -1, -1, -1}, {0, 0, 0, 0, 0}};
+        if (p.table && p.table_stride > 0) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i)  // (index clamped to the row: an entry past the session's keys is never used)
+            w.first_ids[i] = table_row[min((tb * kBN + 16 * i) >> p.log_bs, p.table_stride - 1)];
+        }
+        p.items[pos] = w;
+      } else {
+        atomicOr(&flags_s, 2);  // more units than total_new_tokens and n_sessions allow: the lengths on the device
+                                // disagree with the host's bounds, and this piece of work is not done
+      }
+    }
+  };
+  if (cached) {
+#pragma unroll
+    for (int r = 0; r < kSchedCached; ++r)
+      if (r < n_rounds) emit(uc[r], cc[r]);
+  } else {
     int carry_c = 0, carry_m = 0;
     for (int base = 0; base < U; base += kSchedThreads) {
-      const Cut c = cut_round(base, carry_c, carry_m);
-      if (c.n_real == 0) continue;
-      if (c.n_real > 1) {
-        atomicMax(&n_pslot_s, c.pslot0 + c.n_real);
-        atomicMax(&n_split_s, c.merge + 1);
-      }
-      const int cu_s = cu_of[c.u.s];
-      const int32_t* table_row = p.table + (int64_t)c.u.s * p.table_stride;
-      for (int ch = 0; ch < c.n_real; ++ch) {
-        const int tb = ch * c.len, te = min(c.u.nt, tb + c.len);
-        const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
-        if (pos < p.items_bound) {
-          WorkItem w{c.u.s, c.u.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, c.u.N, c.u.P,
-                     c.merge, c.pslot0, c.n_real, {-1, -1, -1, -1, -1, -1, -1, -1}, {0, 0, 0, 0, 0}};
-          if (p.table && p.table_stride > 0) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)  // (index clamped to the row: an entry past the session's keys is never used)
-              w.first_ids[i] = table_row[min((tb * kBN + 16 * i) >> p.log_bs, p.table_stride - 1)];
-          }
-          p.items[pos] = w;
-        } else
-          atomicOr(&flags_s, 2);  // more units than total_new_tokens and n_sessions allow: the lengths on the device
-                                  // disagree with the host's bounds, and this piece of work is not done
-      }
+      const Unit un = unit(base + tid);
+      emit(un, cut_of(un, carry_c, carry_m));
     }
   }
   __syncthreads();
