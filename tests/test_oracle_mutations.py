@@ -14,7 +14,10 @@ MUTATIONS = {
     "kv_order_swapped_in_buffer": ("((int64_t)2 * l + kv) * prefix_lens[s]", "((int64_t)2 * l + 1 - kv) * prefix_lens[s]"),
     "buffer_token_major_instead_of_layer_major": ("(offsets[s] * 2 * n_layers + ((int64_t)2 * l + kv) * prefix_lens[s] + t) * row",
                                                   "((offsets[s] + t) * 2 * n_layers + ((int64_t)2 * l + kv)) * row"),
-    "slot_index_wrong": ("const int64_t o = t % block_size;\n  *pool_elem", "const int64_t o = (t + 1) % block_size;\n  *pool_elem"),
+    "slot_index_wrong": ("const int64_t o = t % block_size;\n  *pool_elem = (int64_t)l * layer_stride + b * block_stride + o * row;\n  *buf_elem = (offsets[s] * 2 * n_layers",
+                         "const int64_t o = (t + 1) % block_size;\n  *pool_elem = (int64_t)l * layer_stride + b * block_stride + o * row;\n  *buf_elem = (offsets[s] * 2 * n_layers"),
+    "slot_index_wrong_batch_layers": ("const int64_t o = t % block_size;\n  *pool_elem = (int64_t)l * layer_stride + b * block_stride + o * row;\n  *buf_elem = ((int64_t)l * 2 * total",
+                                      "const int64_t o = (t + 1) % block_size;\n  *pool_elem = (int64_t)l * layer_stride + b * block_stride + o * row;\n  *buf_elem = ((int64_t)l * 2 * total"),
     "gqa_head_modulo": ("const int32_t g = h / G;", "const int32_t g = h % n_kv_heads;"),
     "causal_excludes_self": ("const int64_t n_keys = (int64_t)P + i + 1;", "const int64_t n_keys = (int64_t)P + i;"),
     "causal_sees_future": ("const int64_t n_keys = (int64_t)P + i + 1;", "const int64_t n_keys = (int64_t)P + i + 2;"),
