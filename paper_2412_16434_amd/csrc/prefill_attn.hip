@@ -155,7 +155,7 @@ struct WorkItem {   // 96 bytes
   int32_t pad[5];
 };
 struct MergeItem {  // 16 bytes: a short turn that the decode kernel cut at the boundary of two shares
-  int32_t s, t0, pslot0, n_chunks;
+  int32_t s, t0, pslot0, n_chunks;  // pslot0: the decode kernel's slot (2 * workgroup + 0 / 1) of the first piece
 };
 // Header of the workspace (ints): counts written by the scheduler, a counter of the decode kernel, flags, and a 256-byte
 // page of zeros (source of absent key rows).
@@ -165,6 +165,11 @@ constexpr int kHdrItems = 0, kHdrChunk = 1, kHdrSplitUnits = 2, kHdrPslots = 3, 
 static_assert(kHdrFlags < kAttnHdrInts && kAttnHdrInts <= 64, "the counts and flags lie in front of the zero page");
 constexpr int kZeroPageInt = 64;
 constexpr int kPartialFloats = 256 * 66;  // per workgroup: 64 accumulators + running max + running sum per thread
+// A piece of a short turn (decode kernel): only the session's own rows, r = head * N + token (at most 32), packed:
+// rows x 128 accumulators, then the rows' softmax references, then their sums.  Whole 128-byte lines are written and
+// nothing else: a slot in the layout above would be 528 lines with 32 of their 128 bytes dirty, and writing such lines
+// back cost the decode step 13 % of its time.
+constexpr int kDecPartialFloats = 32 * 130;
 
 struct SchedParams {
   const int32_t* cu_new_lens;
@@ -492,7 +497,8 @@ struct MfmaParams {
   const int32_t* dec_s;
   const int32_t* dec_off;
   MergeItem* dec_merges;
-  int32_t dec_pslot_base, dec_merges_bound;
+  int32_t dec_merges_bound;
+  float* dec_partials;  // [2 * workgroups per kv-head][n_kv_heads][kDecPartialFloats], behind the work items' slots
 };
 
 
@@ -1349,22 +1355,36 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
     // Two slots per workgroup: 2 * wg for a segment that starts where the range starts (a session continued from
     // the range before), 2 * wg + 1 for one that starts inside it.  The pieces of a session are then its first one
     // and, for every further range it reaches into, that range's even slot; the workgroup that has the first piece
-    // puts the session on the merge list (negative count: this slot rule).
-    const int pslot = p.dec_pslot_base + 2 * wg + (at_range_start ? 0 : 1);
+    // puts the session on the merge list.
+    const int pslot = 2 * wg + (at_range_start ? 0 : 1);
     if (u_begin == 0 && kvh == 0 && tid == 0) {
       const int last_wg = (unit_end - 1) / per_wg;
       const int mi = atomicAdd(p.hdr + kHdrDecMerges, 1);  // at most one per workgroup: the list has room for all
       if (mi < p.dec_merges_bound) p.dec_merges[mi] = MergeItem{s, 0, pslot, last_wg - wg + 1};
     }
-    // the merge kernel's layout: thread (row >> 5) * 64 + g2 * 32 + (row & 31) with row = head * BMT + token
-    const int row = hh * BMT + tt;
-    float* part = p.partials + ((int64_t)pslot * Hkv + kvh) * kPartialFloats + (row >> 5) * 64 + g2 * 32 + (row & 31);
+    // The piece goes through LDS into the packed layout, so that every store instruction writes whole lines.
+    const int rows = G * N;
+    const int n_floats = rows * 130;
+    const int n_padded = (n_floats + 31) & ~31;
+    float* const stage = reinterpret_cast<float*>(lds);
+    const float l_row = sum_across_halves(L);
+    __syncthreads();  // every thread has taken its values out of the exchange area
+    if (q_valid) {
+      const int r = hh * N + tt;
+      float* so = stage + r * 128 + 32 * wave + 4 * g2;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) part[(wave * 16 + e) * 256] = acc[e];
-    if (wave == 0) {
-      part[64 * 256] = M;
-      part[65 * 256] = L;
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) so[8 * i + j] = acc[4 * i + j];
+      if (wave == 0 && g2 == 0) {
+        stage[rows * 128 + r] = M;
+        stage[rows * 129 + r] = l_row;
+      }
     }
+    if (n_floats + tid < n_padded) stage[n_floats + tid] = 0.f;
+    __syncthreads();
+    float* part = p.dec_partials + ((int64_t)pslot * Hkv + kvh) * kDecPartialFloats;
+    for (int idx = tid; idx < n_padded; idx += 256) part[idx] = stage[idx];
   }
   __syncthreads();  // the exchange area becomes tile buffers again
   }
@@ -1372,58 +1392,38 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p)
 
 // Combine the pieces of a short turn that the decode kernel cut at the boundaries of its workgroups' shares:
 // out = sum_c w_c O_c / sum_c w_c l_c with w_c = 2^(m_c - max_c m_c), m_c being the piece's softmax reference in log2
-// units (-inf: the piece saw no key of the row).  The first piece is in pslot0, piece c >= 1 in the even slot of the
-// c-th workgroup after the one that wrote pslot0.
-// One workgroup per (session, kv-head, 32-wide slice of d), same thread -> (row, d) mapping as attn_mfma_kernel.
+// units (-inf: the piece saw no key of the row).  The first piece is in slot pslot0, piece c >= 1 in the even slot of
+// the c-th workgroup after the one that wrote pslot0; pieces are added in that order.
+// One workgroup per (session, kv-head); a thread per (row, d) element of the packed pieces.
 template <int G>
 __global__ __launch_bounds__(256) void attn_decode_merge_kernel(const MfmaParams p) {
-  constexpr int BMT = 128 / G;
   const int Hkv = p.n_kv_heads;
-  const int dt = blockIdx.x & 3;
-  const int rest = blockIdx.x >> 2;
-  const int mi = rest / Hkv;
+  const int mi = blockIdx.x / Hkv;
   if (mi >= min(p.hdr[kHdrDecMerges], p.dec_merges_bound)) return;
-  const int kvh = rest - mi * Hkv;
+  const int kvh = blockIdx.x - mi * Hkv;
   const MergeItem m = p.dec_merges[mi];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int n = lane & 31, g2 = lane >> 5;
-  const int r = (tid >> 6) * 32 + n;
-  const int hh = r / BMT;
-  const int tok = m.t0 + (r - hh * BMT);
   const int cu_s = p.cu_new_lens[m.s];
   const int N = p.cu_new_lens[m.s + 1] - cu_s;
-  const int first_wg = (m.pslot0 - p.dec_pslot_base) >> 1;
-  auto chunk = [&](int ch) {
-    const int slot = ch == 0 ? m.pslot0 : p.dec_pslot_base + 2 * (first_wg + ch);
-    return p.partials + ((int64_t)slot * Hkv + kvh) * kPartialFloats + tid;
+  const int rows = G * N;
+  const int first_wg = m.pslot0 >> 1;
+  auto piece = [&](int c) {
+    const int slot = c == 0 ? m.pslot0 : 2 * (first_wg + c);
+    return p.dec_partials + ((int64_t)slot * Hkv + kvh) * kDecPartialFloats;
   };
-  // Rows past the session's new tokens hold nothing (a one-token turn fills 4 of a slot's 128 rows): their lanes, in
-  // pairs l and l ^ 32 (the two halves of one row), read no partial results.  No barrier follows.
-  if (tok >= N) return;
-  float M = -INFINITY;
-  for (int ch = 0; ch < m.n_chunks; ++ch) M = fmaxf(M, chunk(ch)[64 * 256]);
-  float acc[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-  float L = 0.f;
-  for (int ch = 0; ch < m.n_chunks; ++ch) {
-    const float* part = chunk(ch);
-    const float mc = part[64 * 256];
-    const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);  // references are in log2 units
-    L += w * part[65 * 256];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = fmaf(w, part[(dt * 16 + e) * 256], acc[e]);
-  }
-  const float l_tot = sum_across_halves(L);
-  const float inv = 1.0f / l_tot;
-  __bf16* op = p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + (kvh * G + hh)) * kD;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    bf16x4 v;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = (__bf16)(acc[4 * i + j] * inv);
-    *reinterpret_cast<bf16x4*>(op + 32 * dt + 4 * g2 + 8 * i) = v;
+  for (int idx = threadIdx.x; idx < rows * 128; idx += 256) {
+    const int r = idx >> 7, d = idx & 127;
+    float M = -INFINITY;
+    for (int c = 0; c < m.n_chunks; ++c) M = fmaxf(M, piece(c)[rows * 128 + r]);
+    float L = 0.f, o = 0.f;
+    for (int c = 0; c < m.n_chunks; ++c) {
+      const float* part = piece(c);
+      const float mc = part[rows * 128 + r];
+      const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);  // references are in log2 units
+      L += w * part[rows * 129 + r];
+      o = fmaf(w, part[idx], o);
+    }
+    const int hh = r / N, tt = r - hh * N;
+    p.out[((int64_t)(cu_s + tt) * p.n_q_heads + (kvh * G + hh)) * kD + d] = (__bf16)(o * (1.0f / L));
   }
 }
 
@@ -1450,8 +1450,8 @@ struct MfmaPlan {
   int32_t bmt, target, target_slots, c_min, coarse, units_bound, items_bound, merges_bound, pslots_bound;
   // decode kernel: whether this call runs it, workgroups per kv-head, first of their 2 * dec_wgs slots, room in its
   // list of sessions cut between shares
-  int32_t dec_mode, dec_wgs, dec_pslot_base, dec_merges_bound;
-  int64_t off_items, off_dec_s, off_dec_off, off_dec_merges, off_merge_cnt, off_partials, total_bytes;
+  int32_t dec_mode, dec_wgs, dec_merges_bound;
+  int64_t off_items, off_dec_s, off_dec_off, off_dec_merges, off_merge_cnt, off_partials, off_dec_partials, total_bytes;
 };
 
 static inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
@@ -1459,7 +1459,6 @@ static inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 static void lay_out(MfmaPlan& pl, int32_t n_sessions, int32_t n_kv_heads) {
   pl.items_bound = pl.units_bound + pl.pslots_bound;  // every unit once, plus one more item per chunk of a split unit
   pl.merges_bound = pl.pslots_bound / 2;              // a split unit has at least two chunks
-  pl.dec_pslot_base = pl.pslots_bound;
   pl.dec_merges_bound = pl.dec_wgs;                   // at most one session starts inside a share and leaves it
   const int32_t ns = n_sessions < kSchedMaxSessions ? n_sessions : kSchedMaxSessions;  // per scheduler slice
   pl.off_items = align256(kHdrInts * 4);
@@ -1468,7 +1467,8 @@ static void lay_out(MfmaPlan& pl, int32_t n_sessions, int32_t n_kv_heads) {
   pl.off_dec_merges = align256(pl.off_dec_off + (int64_t)(ns + 1) * 4);
   pl.off_merge_cnt = align256(pl.off_dec_merges + (int64_t)pl.dec_merges_bound * sizeof(MergeItem));
   pl.off_partials = align256(pl.off_merge_cnt + (int64_t)pl.merges_bound * n_kv_heads * 4);
-  pl.total_bytes = pl.off_partials + (int64_t)(pl.pslots_bound + 2 * pl.dec_wgs) * n_kv_heads * kPartialFloats * 4;
+  pl.off_dec_partials = pl.off_partials + (int64_t)pl.pslots_bound * n_kv_heads * kPartialFloats * 4;
+  pl.total_bytes = pl.off_dec_partials + (int64_t)2 * pl.dec_wgs * n_kv_heads * kDecPartialFloats * 4;
 }
 
 // Sizes that depend only on host-visible bounds and the tuning values, so that the workspace query and the launch
@@ -1619,13 +1619,13 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.dec_s = sp.dec_s;
   p.dec_off = sp.dec_off;
   p.dec_merges = (MergeItem*)(ws + pl.off_dec_merges);
-  p.dec_pslot_base = pl.dec_pslot_base;
+  p.dec_partials = (float*)(ws + pl.off_dec_partials);
   p.dec_merges_bound = pl.dec_merges_bound;
   p.partials = (float*)(ws + pl.off_partials);
 
   const int64_t g_main = (int64_t)pl.items_bound * a.n_kv_heads;
   const int64_t g_dec = (int64_t)pl.dec_wgs * a.n_kv_heads;
-  const int64_t g_merge = (int64_t)pl.dec_merges_bound * a.n_kv_heads * 4;
+  const int64_t g_merge = (int64_t)pl.dec_merges_bound * a.n_kv_heads;
   if (g_main > 0x7FFFFFFFLL || g_merge > 0x7FFFFFFFLL) return SYMPH_EUNSUPPORTED;
   // The scheduler keeps one table entry per session in LDS: larger batches run as consecutive slices of sessions
   // (same stream, same workspace; the bounds of the whole batch cover every slice).
