@@ -195,17 +195,40 @@ __device__ __forceinline__ int unit_tiles(int P, int N, int t0, int bmt) {
   return (P + min(N, t0 + bmt) + kBN - 1) / kBN;
 }
 
+// Inclusive scan over the 64 lanes of a wave with data-parallel moves: shifts by 1, 2, 4, 8 inside each row of 16
+// lanes (a lane without a source adds 0), then the last lane of rows 0 and 2 added to rows 1 and 3, then lane 31 to
+// rows 2 and 3.  (A shuffle per step goes through the LDS crossbar and takes ten times as long.)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_from(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, true);
+}
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_from<0x111, 0xF>(v);  // row_shr:1
+  v += dpp_from<0x112, 0xF>(v);  // row_shr:2
+  v += dpp_from<0x114, 0xF>(v);  // row_shr:4
+  v += dpp_from<0x118, 0xF>(v);  // row_shr:8
+  v += dpp_from<0x142, 0xA>(v);  // row_bcast:15
+  v += dpp_from<0x143, 0xC>(v);  // row_bcast:31
+  return v;
+}
+
+// Maximum over the 64 lanes of a wave of values >= 0 (the same moves as the scan; a lane without a source sees 0);
+// lane 63 holds the result.
+__device__ __forceinline__ int wave_inclusive_max(int v) {
+  v = max(v, dpp_from<0x111, 0xF>(v));
+  v = max(v, dpp_from<0x112, 0xF>(v));
+  v = max(v, dpp_from<0x114, 0xF>(v));
+  v = max(v, dpp_from<0x118, 0xF>(v));
+  v = max(v, dpp_from<0x142, 0xA>(v));
+  v = max(v, dpp_from<0x143, 0xC>(v));
+  return v;
+}
+
 // Inclusive scan of two ints per thread across the 256-thread block; the block totals come back through tot_a, tot_b.
 __device__ __forceinline__ void block_inclusive_scan2(int& a, int& b, int (*wave_sums)[2], int& tot_a, int& tot_b) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int ua = __shfl_up(a, o), ub = __shfl_up(b, o);
-    if (lane >= o) {
-      a += ua;
-      b += ub;
-    }
-  }
+  a = wave_inclusive_scan(a);
+  b = wave_inclusive_scan(b);
   __syncthreads();
   if (lane == 63) {
     wave_sums[w][0] = a;
@@ -316,6 +339,16 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   const int n_rounds = (U + kSchedThreads - 1) / kSchedThreads;
   const bool cached = n_rounds <= kSchedCached;
   Unit uc[kSchedCached];
+  // Block ids of a unit's first two key tiles: what its first (for most units: only) work item carries.  Their loads
+  // start here and return while the passes below run.
+  int ids0[kSchedCached][8];
+  const bool has_table = p.table && p.table_stride > 0;
+  auto first_ids_of = [&](int s, int first_tile, int (&ids)[8]) {
+    const int32_t* table_row = p.table + (int64_t)s * p.table_stride;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)  // (index clamped to the row: an entry past the session's keys is never used)
+      ids[i] = has_table ? table_row[min((first_tile * kBN + 16 * i) >> p.log_bs, p.table_stride - 1)] : -1;
+  };
   // pass 1: total number of (unit, key tile) pairs
   unsigned long long mine = 0;
   if (cached) {
@@ -323,11 +356,22 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     for (int r = 0; r < kSchedCached; ++r) {
       uc[r] = unit(r * kSchedThreads + tid);
       mine += (unsigned long long)uc[r].nt;
+      if (r < n_rounds && uc[r].nt > 0) first_ids_of(uc[r].s, 0, ids0[r]);
     }
   } else {
     for (int u = tid; u < U; u += kSchedThreads) mine += (unsigned long long)unit(u).nt;
   }
-  if (mine) atomicAdd(&total_tiles_s, mine);
+  // (summed inside each wave first: atomics of all threads on the one LDS word run one after the other, and took
+  // longer than every other step of this kernel)
+  {
+    // three scans of 20-bit pieces: none can overflow an int over 64 lanes (a thread's count is below 2^60)
+    const int s0 = wave_inclusive_scan((int)(mine & 0xFFFFFull));
+    const int s1 = wave_inclusive_scan((int)((mine >> 20) & 0xFFFFFull));
+    const int s2 = wave_inclusive_scan((int)(mine >> 40));
+    const unsigned long long wave_total =
+        ((unsigned long long)(unsigned)s2 << 40) + ((unsigned long long)(unsigned)s1 << 20) + (unsigned)s0;
+    if ((tid & 63) == 63 && wave_total) atomicAdd(&total_tiles_s, wave_total);
+  }
   __syncthreads();
   if (tid == 0) {
     // With at least two workgroup-sized units per slot, longest-first dispatch balances well without splitting
@@ -376,6 +420,14 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
       c.n_real = 1;
       atomicOr(&flags_s, 1);
     }
+    // slots and counters in use = the largest prefix sums that fitted (one LDS atomic per wave, not per unit: atomics
+    // of many lanes on one word run one after the other)
+    const int end_c = wave_inclusive_max(want && fits ? carry_c + ic : 0);
+    const int end_m = wave_inclusive_max(want && fits ? carry_m + im : 0);
+    if ((threadIdx.x & 63) == 63 && end_c) {
+      atomicMax(&n_pslot_s, end_c);
+      atomicMax(&n_split_s, end_m);
+    }
     if (c.n_real <= 1) {
       c.pslot0 = -1;
       c.merge = -1;
@@ -411,52 +463,58 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   __syncthreads();
   if (tid < kSchedBuckets) {  // wave 0: exclusive prefix sum, hist[b] becomes the first list position of bucket b
     const int h = hist[tid];
-    int incl = h;
-#pragma unroll
-    for (int o = 1; o < kSchedBuckets; o <<= 1) {
-      const int up = __shfl_up(incl, o);
-      if (tid >= o) incl += up;
-    }
+    const int incl = wave_inclusive_scan(h);
     hist[tid] = incl - h;
     if (tid == kSchedBuckets - 1) n_items_s = incl;
   }
   __syncthreads();
   // pass 3: emit items
-  auto emit = [&](const Unit& un, const Cut& c) {
+  auto emit = [&](const Unit& un, const Cut& c, const int (*ids_first)[8]) {  // ids_first: of chunk 0, or null
     if (c.n_real == 0) return;
-    if (c.n_real > 1) {
-      atomicMax(&n_pslot_s, c.pslot0 + c.n_real);
-      atomicMax(&n_split_s, c.merge + 1);
-    }
     const int cu_s = cu_of[un.s];
-    const int32_t* table_row = p.table + (int64_t)un.s * p.table_stride;
-    for (int ch = 0; ch < c.n_real; ++ch) {
-      const int tb = ch * c.len, te = min(un.nt, tb + c.len);
-      const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
-      if (pos < p.items_bound) {
-        WorkItem w{un.s, un.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, un.N, un.P,
-                   c.merge, c.pslot0, c.n_real, {-1, -1, -1, -1, -1, -1, -1, -1}, {0, 0, 0, 0, 0}};
-        if (p.table && p.table_stride > 0) {
+    // four chunks at a time: their table reads are issued together, before the first item is written (one wait for
+    // memory per group instead of one per chunk)
+    for (int ch0 = 0; ch0 < c.n_real; ch0 += 4) {
+      int ids[4][8];
 #pragma unroll
-          for (int i = 0; i < 8; ++i)  // (index clamped to the row: an entry past the session's keys is never used)
-            w.first_ids[i] = table_row[min((tb * kBN + 16 * i) >> p.log_bs, p.table_stride - 1)];
+      for (int k = 0; k < 4; ++k) {
+        const int ch = ch0 + k;
+        if (ch >= c.n_real) break;
+        if (ch == 0 && ids_first) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) ids[k][i] = (*ids_first)[i];
+        } else {
+          first_ids_of(un.s, ch * c.len, ids[k]);
         }
-        p.items[pos] = w;
-      } else {
-        atomicOr(&flags_s, 2);  // more units than total_new_tokens and n_sessions allow: the lengths on the device
-                                // disagree with the host's bounds, and this piece of work is not done
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int ch = ch0 + k;
+        if (ch >= c.n_real) break;
+        const int tb = ch * c.len, te = min(un.nt, tb + c.len);
+        const int pos = atomicAdd(&hist[bucket_of(te - tb)], 1);
+        if (pos < p.items_bound) {
+          WorkItem w{un.s, un.t0, tb, te, c.n_real > 1 ? c.pslot0 + ch : -1, cu_s, un.N, un.P,
+                     c.merge, c.pslot0, c.n_real, {-1, -1, -1, -1, -1, -1, -1, -1}, {0, 0, 0, 0, 0}};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) w.first_ids[i] = ids[k][i];
+          p.items[pos] = w;
+        } else {
+          atomicOr(&flags_s, 2);  // more units than total_new_tokens and n_sessions allow: the lengths on the device
+                                  // disagree with the host's bounds, and this piece of work is not done
+        }
       }
     }
   };
   if (cached) {
 #pragma unroll
     for (int r = 0; r < kSchedCached; ++r)
-      if (r < n_rounds) emit(uc[r], cc[r]);
+      if (r < n_rounds) emit(uc[r], cc[r], &ids0[r]);
   } else {
     int carry_c = 0, carry_m = 0;
     for (int base = 0; base < U; base += kSchedThreads) {
       const Unit un = unit(base + tid);
-      emit(un, cut_of(un, carry_c, carry_m));
+      emit(un, cut_of(un, carry_c, carry_m), nullptr);
     }
   }
   __syncthreads();
