@@ -592,22 +592,22 @@ def write_traffic_summary(args):
                 for r in csv.DictReader(fh):
                     if r.get("Counter_Name") == counter:
                         acc.setdefault(r["Kernel_Name"], {}).setdefault(int(r["Grid_Size"]), []).append(float(r["Counter_Value"]))
-        return {k: (sum(g[max(g)]) / len(g[max(g)]), len(g[max(g)])) for k, g in acc.items()}
+        return {k: (sum(g[max(g)]) / len(g[max(g)]), len(g[max(g)]), max(g)) for k, g in acc.items()}
     fetch, write = means(args.write_traffic_summary[0], "FETCH_SIZE"), means(args.write_traffic_summary[1], "WRITE_SIZE")
 
     def pick(table, *subs):
         hits = [(k, v) for k, v in table.items() if all(s in k for s in subs)]
         if not hits:
             raise SystemExit(f"no kernel matching {subs} in the counter files")
-        n = sum(v[1] for _, v in hits)
-        return sum(v[0] * v[1] for _, v in hits) / n, n
+        _, v = max(hits, key=lambda kv: kv[1][2])   # of several instantiations, the one with the largest launch
+        return v[0], v[1]
     copy_f, _ = pick(fetch, "device_copy_kernel")
     copy_w, _ = pick(write, "device_copy_kernel")
     unit_f, unit_w = payload / copy_f, payload / copy_w          # bytes per count
     rows, line = [], []
     for label, key, subs, algo in (
-            ("kv_pack", "kv_pack", ("kv_migrate_kernel", "true, 1,"), 2.0 * payload),
-            ("kv_unpack", "kv_unpack", ("kv_migrate_kernel", "false, 2,"), 2.0 * payload),
+            ("kv_pack", "kv_pack", ("kv_migrate", "kernel<unsigned int __vector(4), true,"), 2.0 * payload),
+            ("kv_unpack", "kv_unpack", ("kv_migrate", "kernel<unsigned int __vector(4), false,"), 2.0 * payload),
             ("prefix_prefill_attn (main kernel)", "attn_mfma", ("attn_mfma_kernel",), float(sess.attn_bytes()))):
         f, nf = pick(fetch, *subs)
         w, nw = pick(write, *subs)
