@@ -674,12 +674,26 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int n = lane & 31;  // query column of this lane inside the wave's 32 rows; also its A-operand row
   const int g2 = lane >> 5;
 
-  // query row of this lane: head-major inside the tile
-  const int r = wave * 32 + n;
-  const int hh = r / BMT;
-  const int tt = r - hh * BMT;
+  // Query row of this lane: head-major inside the tile.  A short turn (all its G * N rows fit one wave) puts them
+  // into wave 0, head-major again, and the other three waves only help with the loads: they skip the matrix and
+  // vector work, which would be padding (a one-token turn fills 4 of the 128 rows), and leave those pipes to the
+  // compute-bound workgroup that shares the CU.
+  const bool short_item = N * G <= 32;
+  const bool wave_works = !short_item || wave == 0;
+  int hh, tt;
+  bool q_valid;
+  if (short_item) {
+    hh = n / max(N, 1);
+    tt = n - hh * N;
+    q_valid = wave == 0 && n < G * N;
+    if (!q_valid) hh = tt = 0;
+  } else {
+    const int r = wave * 32 + n;
+    hh = r / BMT;
+    tt = r - hh * BMT;
+    q_valid = t0 + tt < N;
+  }
   const int tok = t0 + tt;
-  const bool q_valid = tok < N;
   const int head = kvh * G + hh;
 
   bf16x8 qreg[8];
@@ -920,15 +934,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   else
     __builtin_amdgcn_s_waitcnt(0x0F70 | 4);  // vmcnt(4)
   __syncthreads();
-  qk(K0, s_even);
+  if (wave_works) qk(K0, s_even);
 #pragma unroll
   for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];  // ids of tile b+1
   fetch_ids(tile_begin + 2);                      // taken at the top of the first iteration
-  float mb_cur;     // reference of the exponentials, in log2 units
-  bf16x8 pb[2][2];  // P(j); its first half is produced one block ahead of the second
-  mask(s_even, tile_begin);
-  raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile
-  softmax_exp_half(s_even[0], mb_cur, pb[0]);
+  float mb_cur = 0.f;  // reference of the exponentials, in log2 units
+  bf16x8 pb[2][2];     // P(j); its first half is produced one block ahead of the second
+  if (wave_works) {
+    mask(s_even, tile_begin);
+    raise_reference(s_even, mb_cur);   // first reference: the maximum of the first tile
+    softmax_exp_half(s_even[0], mb_cur, pb[0]);
+  }
   // Every wave has read all of K0 for the first product before any wave overwrites it (the first iteration loads
   // K(tile_begin + 2) into K0), and V0 and K1 have landed for all waves.  Later iterations end with the same pair.
   wait_loads_and_sync();
@@ -950,6 +966,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
       for (int i = 0; i < 4; ++i) ids[i] = keep[i];
     }
     if (j + 2 < tile_end) issue_tile(k_bytes, p.k_new, k_same, j + 2);
+    if (wave_works) {
     // ---- block A
     qk(k_other, s_nxt);                          // S(j+1)   (garbage, and discarded below, when j+1 == tile_end)
     softmax_exp_half(s_cur[1], mb_cur, pb[1]);   // second half of P(j)
@@ -1009,6 +1026,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     pb[0][0] = pb_first[0];   // (garbage, and never used, when there was no tile j+1)
     pb[0][1] = pb_first[1];
     asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]));   // computed here, not after the barrier
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) ids_v[i] = ids[i];      // the next V tile is j+2
     wait_loads_and_sync();
