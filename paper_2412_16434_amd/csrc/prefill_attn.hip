@@ -674,25 +674,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int n = lane & 31;  // query column of this lane inside the wave's 32 rows; also its A-operand row
   const int g2 = lane >> 5;
 
-  // Query row of this lane: head-major inside the tile.  A short turn (all its G * N rows fit one wave) puts them
-  // into wave 0, head-major again, and the other three waves only help with the loads: they skip the matrix and
-  // vector work, which would be padding (a one-token turn fills 4 of the 128 rows), and leave those pipes to the
-  // compute-bound workgroup that shares the CU.
-  const bool short_item = N * G <= 32;
-  const bool wave_works = !short_item || wave == 0;
-  int hh, tt;
-  bool q_valid;
-  if (short_item) {
-    hh = n / max(N, 1);
-    tt = n - hh * N;
-    q_valid = wave == 0 && n < G * N;
-    if (!q_valid) hh = tt = 0;
-  } else {
-    const int r = wave * 32 + n;
-    hh = r / BMT;
-    tt = r - hh * BMT;
-    q_valid = t0 + tt < N;
-  }
+  // Query row of this lane.  The tile's 128 / G tokens are dealt to the waves in order, 32 / G tokens x G heads each
+  // (head-major inside the wave), so that the tokens a tile does not have (a session's last tile, a short turn) leave
+  // WHOLE waves without rows.  Such a wave only issues its share of the K,V loads and keeps the barriers: it skips the
+  // matrix and vector work, which would be padding, and leaves those pipes to the workgroup that shares the CU (a
+  // one-token turn fills 4 of the 128 rows: all in wave 0).
+  constexpr int TW = BMT / 4;  // tokens per wave
+  const int hh = n / TW;
+  const int tt = wave * TW + (n - hh * TW);
+  const bool q_valid = t0 + tt < N;
+  const bool wave_works = t0 + wave * TW < N;
   const int tok = t0 + tt;
   const int head = kvh * G + hh;
 
