@@ -572,8 +572,8 @@ def measure_config(args, name: str) -> dict:
     return out
 
 
-def write_traffic_summary(args):
-    """profiles/bench_<config>_hbm_traffic.md from the counter csv files of two rocprofv3 runs of this script (one with
+def write_traffic_summary(args, out_dir=None):
+    """profiles/bench_<config>_hbm_traffic.md (or the same file name under out_dir) from the counter csv files of two rocprofv3 runs of this script (one with
     --pmc FETCH_SIZE, one with --pmc WRITE_SIZE).  The plain copy kernel of known size in the same runs gives the unit
     of each counter on this machine; every other kernel's readings are scaled by it."""
     import csv
@@ -636,10 +636,11 @@ Q, O, K_new, V_new.  bench.py reads the next line for `roofline.traffic`:
 
 traffic_bytes_per_launch: {' '.join(line)}
 """
-    path = os.path.join(PROFILES, f"bench_{cfg.name}_hbm_traffic.md")
+    path = os.path.join(out_dir or PROFILES, f"bench_{cfg.name}_hbm_traffic.md")
     with open(path, "w") as f:
         f.write(text)
     print(path)
+    return path
 
 
 def main():
