@@ -657,8 +657,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
   const int Hkv = p.n_kv_heads;
   const int item_idx = blockIdx.x / Hkv;
   __shared__ int merges_here;  // set for the chunk of a split unit that arrives last
-  const WorkItem it = p.items[item_idx];  // the array covers the whole grid: read before the count is known
-  if (item_idx >= p.hdr[kHdrItems]) return;
+  // The array covers the whole grid, so the item is read beside the count, not after it: one trip to memory less in
+  // front of the first K,V loads.  (The empty statement makes the compiler issue both loads before the branch.)
+  const WorkItem it = p.items[item_idx];
+  const int n_items = p.hdr[kHdrItems];
+  asm volatile("" ::"s"(it.s), "s"(it.pslot), "s"(it.n_chunks), "s"(it.first_ids[0]), "s"(it.first_ids[7]), "s"(n_items));
+  if (item_idx >= n_items) return;
   const int kvh = blockIdx.x - item_idx * Hkv;
   const int s = it.s;
   const int t0 = it.t0;
@@ -1111,7 +1115,6 @@ constexpr int kDecXchBytes = 4 * 66 * 64 * 4;  // exchange area at the end: per 
 
 template <int G, int LB>
 __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const MfmaParams p) {
-  constexpr int BMT = 128 / G;   // row mapping of the partial results (shared with the merge kernel)
   constexpr int BMTD = 32 / G;   // query tokens this kernel covers per session
   static_assert(kDecXchBytes >= 4 * kDecWaveBytes, "the exchange area holds the tile buffers");
   __shared__ __attribute__((aligned(16))) char lds[kDecXchBytes];
