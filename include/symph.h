@@ -214,7 +214,8 @@ typedef struct {
   int32_t coarse;      /* > 0 (default): with at least two units per slot only the longest units are split; < 0: every
                           unit is cut so that there are about two pieces per slot */
   int32_t decode;      /* > 0 (default): decode steps (see max_new_len above) take the key-splitting kernel; < 0: never */
-  int32_t decode_wgs;  /* workgroups of that kernel, summed over the kv-heads (default 512) */
+  int32_t decode_wgs;  /* that kernel runs 4 * decode_wgs waves, one per (key range, kv-head): 4 * decode_wgs /
+                          n_kv_heads ranges (default 512: with 8 kv-heads one 8-wave workgroup per compute unit) */
   int32_t reserved[3]; /* 0 */
 } symph_attn_tuning;
 
