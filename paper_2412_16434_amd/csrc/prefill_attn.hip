@@ -556,7 +556,8 @@ struct MfmaParams {
   const int32_t* dec_off;
   MergeItem* dec_merges;
   int32_t dec_merges_bound;
-  float* dec_partials;  // [2 * workgroups per kv-head][n_kv_heads][kDecPartialFloats], behind the work items' slots
+  float* dec_partials;  // [2 * key ranges][n_kv_heads][dec_slot_floats], behind the work items' slots
+  int32_t dec_slot_floats;  // room for the packed piece of the longest short turn the call admits (whole lines)
 };
 
 
@@ -1425,7 +1426,7 @@ __global__ __launch_bounds__(64 * HW, HW == 8 ? 1 : 2) void attn_decode_kernel(c
     if (n_floats + lane < n_padded) stage[n_floats + lane] = 0.f;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    float* part = p.dec_partials + ((int64_t)pslot * Hkv + kvh) * kDecPartialFloats;
+    float* part = p.dec_partials + ((int64_t)pslot * Hkv + kvh) * p.dec_slot_floats;
     for (int idx = lane; idx < n_padded; idx += 64) part[idx] = stage[idx];
     __builtin_amdgcn_wave_barrier();
   }
@@ -1450,7 +1451,7 @@ __global__ __launch_bounds__(256) void attn_decode_merge_kernel(const MfmaParams
   const int first_wg = m.pslot0 >> 1;
   auto piece = [&](int c) {
     const int slot = c == 0 ? m.pslot0 : 2 * (first_wg + c);
-    return p.dec_partials + ((int64_t)slot * Hkv + kvh) * kDecPartialFloats;
+    return p.dec_partials + ((int64_t)slot * Hkv + kvh) * p.dec_slot_floats;
   };
   for (int idx = threadIdx.x; idx < rows * 128; idx += 256) {
     const int r = idx >> 7, d = idx & 127;
@@ -1492,7 +1493,7 @@ struct MfmaPlan {
   int32_t bmt, target, target_slots, c_min, coarse, units_bound, items_bound, merges_bound, pslots_bound;
   // decode kernel: whether this call runs it, its key ranges (two slots each per kv-head), room in its
   // list of sessions cut between shares
-  int32_t dec_mode, dec_wgs, dec_merges_bound;
+  int32_t dec_mode, dec_wgs, dec_merges_bound, dec_slot_floats;
   int64_t off_items, off_dec_s, off_dec_off, off_dec_merges, off_merge_cnt, off_partials, off_dec_partials, total_bytes;
 };
 
@@ -1510,7 +1511,7 @@ static void lay_out(MfmaPlan& pl, int32_t n_sessions, int32_t n_kv_heads) {
   pl.off_merge_cnt = align256(pl.off_dec_merges + (int64_t)pl.dec_merges_bound * sizeof(MergeItem));
   pl.off_partials = align256(pl.off_merge_cnt + (int64_t)pl.merges_bound * n_kv_heads * 4);
   pl.off_dec_partials = pl.off_partials + (int64_t)pl.pslots_bound * n_kv_heads * kPartialFloats * 4;
-  pl.total_bytes = pl.off_dec_partials + (int64_t)2 * pl.dec_wgs * n_kv_heads * kDecPartialFloats * 4;
+  pl.total_bytes = pl.off_dec_partials + (int64_t)2 * pl.dec_wgs * n_kv_heads * pl.dec_slot_floats * 4;
 }
 
 // Sizes that depend only on host-visible bounds and the tuning values, so that the workspace query and the launch
@@ -1530,6 +1531,9 @@ static bool make_plan(MfmaPlan& pl, int32_t n_sessions, int32_t n_q_heads, int32
   // turns are memory-bound pieces that share the CUs with the compute-bound ones inside the main kernel, which
   // measured faster than two kernels one after the other.
   pl.dec_mode = tu.decode && max_new_len >= 1 && max_new_len * G <= 32;
+  // The decode kernel takes the sessions with at most max_new_len new tokens (longer ones, if the bound was understated,
+  // are work items), so a piece has at most G * max_new_len rows of 130 values: slots of that size, in whole lines.
+  pl.dec_slot_floats = pl.dec_mode ? ((G * max_new_len * 130 + 31) & ~31) : 0;
   // ranges of the decode kernel: one wave per (range, kv-head), as many waves as decode_wgs workgroups of four would have
   pl.dec_wgs = pl.dec_mode ? (4 * tu.decode_wgs / n_kv_heads < 1 ? 1 : 4 * tu.decode_wgs / n_kv_heads) : 0;
   // Chunks of split units: a unit is split when it has more than C tiles, C >= total tiles * kv-heads / target, so
@@ -1627,7 +1631,7 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   sp.merges_bound = pl.merges_bound;
   sp.pslots_bound = pl.pslots_bound;
   sp.hdr = (int32_t*)ws;
-  sp.bmt_dec = pl.dec_mode ? 32 / G : 0;
+  sp.bmt_dec = pl.dec_mode ? a.max_new_len : 0;   // (<= 32 / G in this mode)
   sp.dec_s = (int32_t*)(ws + pl.off_dec_s);
   sp.dec_off = (int32_t*)(ws + pl.off_dec_off);
   sp.items = (WorkItem*)(ws + pl.off_items);
@@ -1663,6 +1667,7 @@ static int32_t launch_mfma(const AttnArgs& a, hipStream_t stream) {
   p.dec_off = sp.dec_off;
   p.dec_merges = (MergeItem*)(ws + pl.off_dec_merges);
   p.dec_partials = (float*)(ws + pl.off_dec_partials);
+  p.dec_slot_floats = pl.dec_slot_floats;
   p.dec_merges_bound = pl.dec_merges_bound;
   p.partials = (float*)(ws + pl.off_partials);
 
