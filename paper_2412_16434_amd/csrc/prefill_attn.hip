@@ -1541,23 +1541,26 @@ static bool make_plan(MfmaPlan& pl, int32_t n_sessions, int32_t n_q_heads, int32
   pl.pslots_bound = 2 * (pl.target / n_kv_heads + 1);
   lay_out(pl, n_sessions, n_kv_heads);
   if (budget_bytes <= 0 || pl.total_bytes <= budget_bytes) return true;
+  // First the work list gives up its partial-result slots (in a decode step it only serves sessions longer than the
+  // stated bound), then the decode kernel's ranges are halved until its pieces fit, and the work list gets back as
+  // many slots as the room that is left holds.
   const int64_t slot_bytes = (int64_t)n_kv_heads * kPartialFloats * 4;
+  const int32_t wanted = pl.pslots_bound;
+  pl.pslots_bound = 0;
+  lay_out(pl, n_sessions, n_kv_heads);
   while (pl.dec_wgs > 1 && pl.total_bytes > budget_bytes) {
     pl.dec_wgs /= 2;
     lay_out(pl, n_sessions, n_kv_heads);
   }
-  if (pl.total_bytes > budget_bytes) {
-    pl.pslots_bound = 0;
-    lay_out(pl, n_sessions, n_kv_heads);
-    const int64_t per_slot = slot_bytes + (int64_t)sizeof(WorkItem) + 4 * n_kv_heads;
-    const int64_t room = budget_bytes - pl.total_bytes - 4 * 256;  // (the arrays are aligned to 256 bytes)
-    if (room < 0) return false;
-    pl.pslots_bound = (int32_t)(room / per_slot < 0x7FFFFFFF ? room / per_slot : 0x7FFFFFFF) & ~1;
-    const int64_t pieces = (int64_t)(pl.pslots_bound / 2) * n_kv_heads;  // (the bound above, solved for the target)
-    if (pieces < pl.target) pl.target = pieces < n_kv_heads ? n_kv_heads : (int32_t)pieces;
-    if (pl.target_slots > pl.target) pl.target_slots = pl.target;
-    lay_out(pl, n_sessions, n_kv_heads);
-  }
+  const int64_t per_slot = slot_bytes + (int64_t)sizeof(WorkItem) + 4 * n_kv_heads;
+  const int64_t room = budget_bytes - pl.total_bytes - 4 * 256;  // (the arrays are aligned to 256 bytes)
+  if (room < 0) return false;
+  const int64_t fit = room / per_slot;
+  pl.pslots_bound = (int32_t)(fit < wanted ? fit : wanted) & ~1;
+  const int64_t pieces = (int64_t)(pl.pslots_bound / 2) * n_kv_heads;  // (the bound above, solved for the target)
+  if (pieces < pl.target) pl.target = pieces < n_kv_heads ? n_kv_heads : (int32_t)pieces;
+  if (pl.target_slots > pl.target) pl.target_slots = pl.target;
+  lay_out(pl, n_sessions, n_kv_heads);
   return pl.total_bytes <= budget_bytes;
 }
 
