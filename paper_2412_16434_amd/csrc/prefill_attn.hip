@@ -1455,15 +1455,35 @@ __global__ __launch_bounds__(256) void attn_decode_merge_kernel(const MfmaParams
   };
   for (int idx = threadIdx.x; idx < rows * 128; idx += 256) {
     const int r = idx >> 7, d = idx & 127;
-    float M = -INFINITY;
-    for (int c = 0; c < m.n_chunks; ++c) M = fmaxf(M, piece(c)[rows * 128 + r]);
-    float L = 0.f, o = 0.f;
-    for (int c = 0; c < m.n_chunks; ++c) {
-      const float* part = piece(c);
-      const float mc = part[rows * 128 + r];
-      const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);  // references are in log2 units
-      L += w * part[rows * 129 + r];
-      o = fmaf(w, part[idx], o);
+    float M = -INFINITY, L = 0.f, o = 0.f;
+    if (m.n_chunks <= 8) {
+      // the usual case: everything is asked for at once (one trip to memory, not one for the references and another
+      // for the rest), and added in piece order
+      float mc[8], lc[8], oc[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float* part = piece(c < m.n_chunks ? c : 0);
+        mc[c] = c < m.n_chunks ? part[rows * 128 + r] : -INFINITY;
+        lc[c] = part[rows * 129 + r];
+        oc[c] = part[idx];
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) M = fmaxf(M, mc[c]);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float w = (mc[c] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc[c] - M);  // references are in log2 units
+        L += w * lc[c];
+        o = fmaf(w, oc[c], o);
+      }
+    } else {
+      for (int c = 0; c < m.n_chunks; ++c) M = fmaxf(M, piece(c)[rows * 128 + r]);
+      for (int c = 0; c < m.n_chunks; ++c) {
+        const float* part = piece(c);
+        const float mc = part[rows * 128 + r];
+        const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - M);
+        L += w * part[rows * 129 + r];
+        o = fmaf(w, part[idx], o);
+      }
     }
     const int hh = r / N, tt = r - hh * N;
     p.out[((int64_t)(cu_s + tt) * p.n_q_heads + (kvh * G + hh)) * kD + d] = (__bf16)(o * (1.0f / L));
