@@ -98,6 +98,12 @@ def test_attention_edge_cases(oracle_mod, kw):
     (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 2), n_q_heads=32, n_kv_heads=2, n_sessions=6), 32),
     (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 0, 3), block_size=32, n_blocks=256, n_sessions=10), 32),
     (dict(prefix_dist=("uniform", 100, 900), new_dist=("uniform", 1, 3), block_size=64, n_blocks=128, n_sessions=10), 512),
+    # eight kv-heads: the decode kernel's eight-wave workgroups (one wave per head, a barrier per tile); sixteen: two
+    # such groups per key range; twelve: not a multiple of eight, single-wave workgroups
+    (dict(prefix_dist=("uniform", 1, 1200), new_dist=("uniform", 1, 8), n_q_heads=32, n_kv_heads=8, n_sessions=11, n_blocks=1024), 32),
+    (dict(prefix_dist=("uniform", 1, 1200), new_dist=("const", 1), n_q_heads=32, n_kv_heads=8, n_sessions=5, n_blocks=512), 512),
+    (dict(prefix_dist=("uniform", 1, 700), new_dist=("uniform", 1, 16), n_q_heads=32, n_kv_heads=16, n_sessions=7, n_blocks=512), 64),
+    (dict(prefix_dist=("uniform", 1, 700), new_dist=("uniform", 1, 32), n_q_heads=12, n_kv_heads=12, n_sessions=7, n_blocks=512), 64),
 ])
 def test_decode_batches(oracle_mod, kw, n_wgs):
     cfg = _cfg(**kw)
