@@ -178,7 +178,7 @@ int32_t symph_kv_append(const symph_kv_cache* cache, int32_t layer, const void* 
  *   total_new_tokens = T, max_new_len >= max N_s, max_prefix_len >= max P_s (host copies).  total_new_tokens and
  *   n_sessions size the grids and the work list; max_prefix_len is only checked against the table width; max_new_len
  *   only chooses kernels: a batch with max_new_len * (n_q_heads / n_kv_heads) <= 32 is a decode step and its short
- *   turns run in a kernel that splits the keys among waves.  Neither of the two is relied on for memory safety: a
+ *   turns run in a kernel that streams K,V with one wave per kv-head.  Neither of the two is relied on for memory safety: a
  *   session longer than stated is still computed, and computed correctly (a turn with more new tokens than stated is
  *   not a short turn for the device-side scheduler and goes through the general kernel), only not at the best speed.
  *   scale > 0 and finite (fp32).  d_workspace: device scratch of at least
@@ -213,7 +213,7 @@ typedef struct {
   int32_t c_min;       /* shortest piece of a (session, query tile) unit that is split, in 64-key tiles (default 8) */
   int32_t coarse;      /* > 0 (default): with at least two units per slot only the longest units are split; < 0: every
                           unit is cut so that there are about two pieces per slot */
-  int32_t decode;      /* > 0 (default): decode steps (see max_new_len above) take the key-splitting kernel; < 0: never */
+  int32_t decode;      /* > 0 (default): decode steps (see max_new_len above) take the streaming kernel; < 0: never */
   int32_t decode_wgs;  /* that kernel runs 4 * decode_wgs waves, one per (key range, kv-head): 4 * decode_wgs /
                           n_kv_heads ranges (default 512: with 8 kv-heads one 8-wave workgroup per compute unit) */
   int32_t reserved[3]; /* 0 */
