@@ -256,6 +256,7 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   __shared__ int len_new[kSchedMaxSessions], len_prefix[kSchedMaxSessions], cu_of[kSchedMaxSessions];
   __shared__ int wave_sums[4][2];
   __shared__ unsigned long long total_tiles_s;
+  __shared__ int max_nt_s, inv_min_nt_s;  // longest unit, and 0x7FFFFFFF - shortest unit (tiles; units with tiles only)
   __shared__ int hist[kSchedBuckets];
   __shared__ int n_items_s, n_split_s, n_pslot_s, chunk_s, flags_s;
   const int tid = threadIdx.x;
@@ -264,6 +265,8 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   for (int i = tid; i < p.merges_bound * p.n_kv_heads; i += kSchedThreads) p.merge_cnt[i] = 0;
   if (tid == 0) {
     total_tiles_s = 0ull;
+    max_nt_s = 0;
+    inv_min_nt_s = 0;
     n_items_s = 0;
     n_split_s = 0;
     n_pslot_s = 0;
@@ -351,15 +354,23 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
   };
   // pass 1: total number of (unit, key tile) pairs
   unsigned long long mine = 0;
+  int longest = 0, inv_shortest = 0;
+  auto note = [&](int nt) {
+    mine += (unsigned long long)nt;
+    if (nt > 0) {
+      longest = max(longest, nt);
+      inv_shortest = max(inv_shortest, 0x7FFFFFFF - nt);
+    }
+  };
   if (cached) {
 #pragma unroll
     for (int r = 0; r < kSchedCached; ++r) {
       uc[r] = unit(r * kSchedThreads + tid);
-      mine += (unsigned long long)uc[r].nt;
+      note(uc[r].nt);
       if (r < n_rounds && uc[r].nt > 0) first_ids_of(uc[r].s, 0, ids0[r]);
     }
   } else {
-    for (int u = tid; u < U; u += kSchedThreads) mine += (unsigned long long)unit(u).nt;
+    for (int u = tid; u < U; u += kSchedThreads) note(unit(u).nt);
   }
   // (summed inside each wave first: atomics of all threads on the one LDS word run one after the other, and took
   // longer than every other step of this kernel)
@@ -370,7 +381,13 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     const int s2 = wave_inclusive_scan((int)(mine >> 40));
     const unsigned long long wave_total =
         ((unsigned long long)(unsigned)s2 << 40) + ((unsigned long long)(unsigned)s1 << 20) + (unsigned)s0;
-    if ((tid & 63) == 63 && wave_total) atomicAdd(&total_tiles_s, wave_total);
+    longest = wave_inclusive_max(longest);
+    inv_shortest = wave_inclusive_max(inv_shortest);
+    if ((tid & 63) == 63 && wave_total) {
+      atomicAdd(&total_tiles_s, wave_total);
+      atomicMax(&max_nt_s, longest);
+      atomicMax(&inv_min_nt_s, inv_shortest);
+    }
   }
   __syncthreads();
   if (tid == 0) {
@@ -384,6 +401,26 @@ __global__ __launch_bounds__(kSchedThreads) void attn_schedule_kernel(const Sche
     if (c > 0x3FFFFFFF) c = 0x3FFFFFFF;
     while (c < 0x3FFFFFFF && (unsigned long long)c * (unsigned long long)target < tot) ++c;
     while (c > 0 && (unsigned long long)(c - 1) * (unsigned long long)target >= tot) --c;
+    // Units of (nearly) one length, and too few of them for the coarse rule: a single long session, or a batch of
+    // equal ones.  Equal pieces are dispatched in whole rounds, so what counts is rounds x (piece + fixed cost), and
+    // one round of longer pieces can beat two rounds of shorter ones.  Only cuts that are not finer than the one
+    // above are tried (the workspace bounds are derived from it).
+    const long long max_nt = max_nt_s, min_nt = 0x7FFFFFFF - inv_min_nt_s;
+    if (target == p.target && max_nt > 0 && min_nt * 51 >= max_nt * 50 && c > 0) {
+      constexpr long long kFixedTiles = 6;  // a work item's fixed cost (~11 us) in key tiles (~1.9 us)
+      long long best_c = c, best_cost = 0x7FFFFFFFFFFFFFFFll;
+      for (long long k = 1; k <= 64; ++k) {
+        const long long ck = (max_nt + k - 1) / k;
+        if (ck < c) break;
+        const long long rounds = (wg_units * k + p.target_slots - 1) / p.target_slots;
+        const long long cost = rounds * (ck + kFixedTiles);
+        if (cost <= best_cost) {  // (of equal costs the finer cut: more pieces in flight)
+          best_cost = cost;
+          best_c = ck;
+        }
+      }
+      c = best_c;
+    }
     if (c < p.c_min) c = p.c_min;
     chunk_s = (int)c;
   }
