@@ -632,6 +632,38 @@ __device__ __forceinline__ void store_out_row(__bf16* op, const f32x16 (&acc)[4]
     }
 }
 
+// The 32 output rows of a wave through a buffer of its own in LDS: every store instruction then writes whole 128-byte
+// lines (the G heads of a token are neighbours in memory: a wave's rows, in (token, head) order, are 32 / G runs of
+// G x 256 bytes), where the direct form writes 8 bytes per lane, i.e. sixteen separate pieces per line for the L2 to put
+// together.  row_of_lane: this lane's row in (token, head) order; valid_bits: bit m set = row m is written.
+constexpr int kOutRowBytes = 256 + 16;
+__device__ __forceinline__ void store_out_rows_staged(char* stage, __bf16* first_row, int64_t token_stride_elems,
+                                                      int rows_per_token, int row_of_lane, unsigned valid_bits,
+                                                      const f32x16 (&acc)[4], float inv, int g2, int lane) {
+  char* wr = stage + row_of_lane * kOutRowBytes + 8 * g2;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      bf16x4 v;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = (__bf16)(acc[dt][4 * i + j] * inv);
+      *reinterpret_cast<bf16x4*>(wr + 64 * dt + 16 * i) = v;
+    }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int m = 4 * it + (lane >> 4);
+    const int tok = m / rows_per_token, hd = m - tok * rows_per_token;
+    if ((valid_bits >> m) & 1u) {
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(stage + m * kOutRowBytes + 16 * (lane & 15));
+      *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(first_row + tok * token_stride_elems + (int64_t)hd * kD) + 16 * (lane & 15)) = v;
+    }
+  }
+}
+
 // Lanes l and l^32 hold the two halves of one query's keys.  v_permlane32_swap_b32 a, b exchanges lanes 32..63 of a
 // with lanes 0..31 of b, so starting from two copies of x it leaves a = low half twice, b = high half twice.
 // Written as inline assembly: with this compiler the builtin hands back the first register for both results.
@@ -1076,10 +1108,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
     if (j + 1 < tile_end) step(j + 1, std::integral_constant<int, 1>{});
   }
 
+  // rows of this wave in (token, head) order, and which of them exist
+  const int row_m = (n - hh * TW) * G + hh;
+  const int n_tok_here = min(max(N - (t0 + wave * TW), 0), TW);           // tokens of this wave's TW that exist
+  const unsigned valid_bits = n_tok_here * G >= 32 ? 0xFFFFFFFFu : ((1u << (n_tok_here * G)) - 1u);
+  char* const out_stage = wave == 0 ? K0 : (wave == 1 ? K1 : (wave == 2 ? V0 : V1));
+  __bf16* const out_first = p.out + ((int64_t)(cu_s + t0 + wave * TW) * p.n_q_heads + kvh * G) * kD;
   if (it.pslot < 0) {
     const float l_tot = sum_across_halves(l_run);
-    if (q_valid)
-      store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + head) * kD, o_acc, 1.0f / l_tot, g2);
+    if (wave_works)   // (every wave is past the last barrier of the loop: the tile buffers are free)
+      store_out_rows_staged(out_stage, out_first, (int64_t)p.n_q_heads * kD, G, row_m, valid_bits, o_acc, 1.0f / l_tot, g2,
+                            lane);
   } else {
     // Register dump, one float per thread per store: fully coalesced.  The chunks of a unit may run on different XCDs,
     // whose L2 caches do not see each other's lines, so everything that passes between them is written and read at
@@ -1130,8 +1169,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const MfmaParams p) {
         for (int e = 0; e < 16; ++e) o_acc[dt][e] = fmaf(w, peer(src + (dt * 16 + e) * 256), o_acc[dt][e]);
     }
     const float l_tot = sum_across_halves(L);
-    if (q_valid)
-      store_out_row(p.out + ((int64_t)(cu_s + tok) * p.n_q_heads + head) * kD, o_acc, 1.0f / l_tot, g2);
+    if (wave_works)
+      store_out_rows_staged(out_stage, out_first, (int64_t)p.n_q_heads * kD, G, row_m, valid_bits, o_acc, 1.0f / l_tot, g2,
+                            lane);
   }
 }
 
